@@ -1,0 +1,149 @@
+/*
+ * sqmi -- SmoothQuant W8A8 hot path for AMD MI355X (gfx950).  C ABI.
+ *
+ * The library computes a linear layer Y = X W (X [T, C_i], W [C_i, C_o]; Sec. 2) as
+ *     Y = diag(Delta_X) (Xq Wq) diag(Delta_W)                       (Eq. 2)
+ * after the offline smoothing transform X_hat = X diag(s)^-1, W_hat = diag(s) W (Eq. 3) with
+ * s_j = max|X_j|^alpha / max|W_j|^(1-alpha) (Eq. 4), quantizing with the symmetric absmax
+ * quantizer Xq = round(X / Delta), Delta = max|X| / 127 (Eq. 1) at one of the granularities of
+ * Table 2 (O1 per-token dynamic, O2 per-tensor dynamic, O3 per-tensor static), plus the two INT8
+ * batched matmuls of attention (Sec. 4, "Applying ... to Transformer blocks").
+ *
+ * Conventions for every entry point
+ *  - "device" pointers are HIP device memory of the current device, "host" pointers ordinary memory.
+ *  - The caller owns every buffer, workspace included; the library never allocates, frees or keeps
+ *    a pointer.  Calls only enqueue work on `stream` (a hipStream_t passed as void*, NULL = default
+ *    stream) and never synchronize; buffers must stay alive until the stream has run the work.
+ *  - Errors are returned as sq_status; argument errors are detected on the host before any launch.
+ *  - Device tensors must be 16-byte aligned; C_i (the contraction length) must be a multiple of 16.
+ *  - Fixed arithmetic (so that int8 codes are reproducible bit for bit): round-half-to-even;
+ *    X / Delta is evaluated as X * r with r = fl32(127 / absmax) (r = fl32(1 / Delta) in static
+ *    mode); codes lie in [-127, 127] (static mode saturates); absmax = 0 gives Delta = 0 and codes
+ *    0; all scales are fp32; no fused multiply-add in scale arithmetic.  Non-finite inputs:
+ *    unspecified.
+ */
+#ifndef SQMI_H
+#define SQMI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SQ_OK = 0,
+    SQ_ERR_NULL = 1,        /* a required pointer is NULL */
+    SQ_ERR_SHAPE = 2,       /* non-positive / overflowing / inconsistent dimension */
+    SQ_ERR_ALIGN = 3,       /* pointer not 16-byte aligned or C_i / stride not a multiple of 16 */
+    SQ_ERR_UNSUPPORTED = 4, /* enum value or parameter outside the supported set */
+    SQ_ERR_WORKSPACE = 5,   /* workspace missing or smaller than sq_workspace_bytes() */
+    SQ_ERR_HIP = 6          /* the HIP runtime reported an error at launch */
+} sq_status;
+
+typedef enum { SQ_F16 = 0, SQ_BF16 = 1 } sq_dtype;
+
+/* Table 2: activation quantization granularity. */
+typedef enum {
+    SQ_PER_TOKEN_DYNAMIC = 0,  /* O1 */
+    SQ_PER_TENSOR_DYNAMIC = 1, /* O2 */
+    SQ_PER_TENSOR_STATIC = 2   /* O3 */
+} sq_act_mode;
+
+typedef enum {
+    SQ_OP_QUANTIZE_ACT = 0,
+    SQ_OP_PREPARE_WEIGHT = 1,
+    SQ_OP_W8A8_LINEAR = 2,
+    SQ_OP_I8_GEMM_I32 = 3,
+    SQ_OP_W8A8_BMM = 4
+} sq_op;
+
+const char* sq_status_string(sq_status st);
+
+/* Eq. 4 (Sec. 4): s_j = max(x_absmax_j, 1e-5)^alpha / max(w_absmax_j, 1e-5)^(1-alpha), powers in
+ * fp64 rounded to fp32; inv_s_j = fl32(1 / s_j).  Offline, tiny: HOST pointers, computed on the
+ * host.  x_absmax, w_absmax, s: fp32 [c_i]; inv_s: fp32 [c_i] or NULL.  alpha outside [0, 1] ->
+ * SQ_ERR_UNSUPPORTED. */
+sq_status sq_smooth_scales(const float* x_absmax, const float* w_absmax, float alpha, int64_t c_i,
+                           float* s, float* inv_s);
+
+/* Calibration statistic of Eq. 4: out_j = max_t |X_tj|.  x: device [t, c_i] row-major 16-bit;
+ * out: device fp32 [c_i], overwritten. */
+sq_status sq_act_absmax_per_channel(const void* x, sq_dtype dtype, int64_t t, int64_t c_i,
+                                    float* out, void* stream);
+
+/* Weight statistic of Eq. 4: out_j = max_n |W_jn| (row j of W = input channel j).  w: device
+ * [c_i, c_o] row-major 16-bit (the paper's W orientation); out: device fp32 [c_i]. */
+sq_status sq_weight_absmax_per_in_channel(const void* w, sq_dtype dtype, int64_t c_i, int64_t c_o,
+                                          float* out, void* stream);
+
+/* Offline weight preparation (Eq. 3 then Eq. 1, per-tensor as in Table 2):
+ *   W_hat = diag(s) W;  Delta_W = max|W_hat| / 127;  Wq = round(W_hat * fl32(127 / max|W_hat|)).
+ * w: device [c_i, c_o] row-major 16-bit; s: device fp32 [c_i] or NULL (s = 1);
+ * wq: device int8 [c_o, c_i] (transposed: contraction index contiguous); w_scale: device fp32 [1].
+ * workspace: device, >= sq_workspace_bytes(SQ_OP_PREPARE_WEIGHT, ...) bytes. */
+sq_status sq_prepare_weight(const void* w, sq_dtype dtype, const float* s, int64_t c_i, int64_t c_o,
+                            int8_t* wq, float* w_scale, void* workspace, size_t ws_bytes, void* stream);
+
+/* Activation quantization (Eq. 1; granularities of Table 2).
+ * x: device [t, c_i] 16-bit, row stride ldx elements (ldx >= c_i, multiple of 8);
+ * inv_s: device fp32 [c_i] or NULL -- when given, x_hat = fl32(x * inv_s_j) is quantized (the
+ *   "extra scaling" for inputs whose producer cannot absorb 1/s, Sec. 4);
+ * scale: device fp32; written in the dynamic modes ([t] per token, [1] per tensor), read in
+ *   SQ_PER_TENSOR_STATIC ([1], the calibrated Delta);
+ * xq: device int8 [t, c_i] packed;  workspace: device, needed for SQ_PER_TENSOR_DYNAMIC only. */
+sq_status sq_quantize_act(const void* x, sq_dtype dtype, int64_t t, int64_t c_i, int64_t ldx,
+                          const float* inv_s, sq_act_mode mode, float* scale, int8_t* xq,
+                          void* workspace, size_t ws_bytes, void* stream);
+
+/* W8A8 linear layer (Eq. 2) with the dequantizing epilogue fused into the INT8 GEMM:
+ *   acc_tn = sum_j xq[t, j] * wq[n, j]                                   (exact int32)
+ *   v = fl32(float(acc_tn) * fl32(x_scale_t * w_scale)); v += bias_n; v = max(v, 0) if relu;
+ *   v += residual_tn;  y_tn = round_to_16bit(v).
+ * xq: device int8 [t, c_i]; x_scale: device fp32 [t] if x_scale_per_token else [1];
+ * wq: device int8 [c_o, c_i]; w_scale: device fp32 [1];
+ * bias: device fp32 [c_o] or NULL; residual: device [t, c_o] of the output dtype or NULL;
+ * y: device [t, c_o] of dtype `out`.
+ * workspace: device, >= sq_workspace_bytes(SQ_OP_W8A8_LINEAR, t, c_i, c_o) bytes (may be 0). */
+sq_status sq_w8a8_linear(const int8_t* xq, const float* x_scale, int x_scale_per_token,
+                         const int8_t* wq, const float* w_scale, const float* bias,
+                         const void* residual, int relu, void* y, sq_dtype out, int64_t t,
+                         int64_t c_i, int64_t c_o, void* workspace, size_t ws_bytes, void* stream);
+
+/* The raw integer contraction of Eq. 2 (test export: makes the bit-exact int32 gate observable).
+ * acc: device int32 [t, c_o]. */
+sq_status sq_i8_gemm_i32(const int8_t* xq, const int8_t* wq, int32_t* acc, int64_t t, int64_t c_i,
+                         int64_t c_o, void* workspace, size_t ws_bytes, void* stream);
+
+/* INT8 batched matmul of attention (Sec. 4): c[b] = round_to_16bit( fl32( float(a[b] B[b]) * alpha ) ).
+ * a: device int8 [b, m, k]; bm: device int8, [b, n, k] if trans_b (Q K^T) else [b, k, n] (P V);
+ * alpha: HOST scalar (e.g. Delta_Q Delta_K / sqrt(d), or Delta_V / 127);
+ * c: device [b, m, n] of dtype `out`.  Batch strides in elements; k % 16 == 0; for trans_b == 0
+ * also n % 16 == 0. */
+sq_status sq_w8a8_bmm(const int8_t* a, const int8_t* bm, int trans_b, float alpha, void* c,
+                      sq_dtype out, int64_t b, int64_t m, int64_t n, int64_t k, int64_t stride_a,
+                      int64_t stride_b, int64_t stride_c, void* stream);
+
+/* Row softmax kept in 16-bit floating point (Sec. 4 keeps Softmax in FP16) followed by quantization
+ * of the probabilities with the fixed step 1/127: pq = round(p * 127) in [0, 127].
+ * s: device [rows, cols] 16-bit scores, packed; pq: device int8 [rows, cols]. */
+sq_status sq_softmax_quant_p(const void* s, sq_dtype dtype, int64_t rows, int64_t cols, int8_t* pq,
+                             void* stream);
+
+/* LayerNorm whose affine parameters already carry the smoothing factors (gamma_f = gamma / s,
+ * beta_f = beta / s, folded offline as Sec. 4 describes) fused with per-token dynamic quantization:
+ *   x_hat_tj = (x_tj - mean_t) * rstd_t * gamma_f_j + beta_f_j;  then Eq. 1 per token.
+ * x: device [t, c_i] 16-bit packed; gamma_f, beta_f: device fp32 [c_i]; scale: device fp32 [t];
+ * xq: device int8 [t, c_i]. */
+sq_status sq_ln_quantize(const void* x, sq_dtype dtype, int64_t t, int64_t c_i, const float* gamma_f,
+                         const float* beta_f, float eps, float* scale, int8_t* xq, void* stream);
+
+/* Workspace size in bytes for `op` at the given problem size (0 if none is needed).  For
+ * SQ_OP_W8A8_BMM pass (m, k, n) as (t, c_i, c_o). */
+size_t sq_workspace_bytes(sq_op op, int64_t t, int64_t c_i, int64_t c_o);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SQMI_H */

@@ -1,0 +1,228 @@
+"""Thin Python binding of the sqmi C ABI (``include/sqmi.h``): argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU (torch is used for device memory and
+streams, nothing else), passes their pointers and the current HIP stream to ``libsqmi.so`` and
+returns the output tensors.  There is no fallback: if the library is missing or a call fails, an
+exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsqmi.so")
+
+F16, BF16 = 0, 1
+PER_TOKEN_DYNAMIC, PER_TENSOR_DYNAMIC, PER_TENSOR_STATIC = 0, 1, 2
+OP_QUANTIZE_ACT, OP_PREPARE_WEIGHT, OP_W8A8_LINEAR, OP_I8_GEMM_I32, OP_W8A8_BMM = range(5)
+
+EXPORTS = (
+    "sq_status_string", "sq_smooth_scales", "sq_act_absmax_per_channel", "sq_weight_absmax_per_in_channel",
+    "sq_prepare_weight", "sq_quantize_act", "sq_w8a8_linear", "sq_i8_gemm_i32", "sq_w8a8_bmm",
+    "sq_softmax_quant_p", "sq_ln_quantize", "sq_workspace_bytes",
+)
+
+
+class SqmiError(RuntimeError):
+    pass
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libsqmi.so (built by ``paper_2211_10438_amd.build``); fail loudly if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise SqmiError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                            "(hipcc, gfx950) first; there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_float
+        L.sq_status_string.restype = ctypes.c_char_p
+        L.sq_status_string.argtypes = [i32]
+        L.sq_smooth_scales.argtypes = [vp, vp, f32, i64, vp, vp]
+        L.sq_act_absmax_per_channel.argtypes = [vp, i32, i64, i64, vp, vp]
+        L.sq_weight_absmax_per_in_channel.argtypes = [vp, i32, i64, i64, vp, vp]
+        L.sq_prepare_weight.argtypes = [vp, i32, vp, i64, i64, vp, vp, vp, ctypes.c_size_t, vp]
+        L.sq_quantize_act.argtypes = [vp, i32, i64, i64, i64, vp, i32, vp, vp, vp, ctypes.c_size_t, vp]
+        L.sq_w8a8_linear.argtypes = [vp, vp, i32, vp, vp, vp, vp, i32, vp, i32, i64, i64, i64, vp, ctypes.c_size_t, vp]
+        L.sq_i8_gemm_i32.argtypes = [vp, vp, vp, i64, i64, i64, vp, ctypes.c_size_t, vp]
+        L.sq_w8a8_bmm.argtypes = [vp, vp, i32, f32, vp, i32, i64, i64, i64, i64, i64, i64, i64, vp]
+        L.sq_softmax_quant_p.argtypes = [vp, i32, i64, i64, vp, vp]
+        L.sq_ln_quantize.argtypes = [vp, i32, i64, i64, vp, vp, f32, vp, vp, vp]
+        L.sq_workspace_bytes.restype = ctypes.c_size_t
+        L.sq_workspace_bytes.argtypes = [i32, i64, i64, i64]
+        for name in EXPORTS:
+            getattr(L, name)
+        _lib = L
+    return _lib
+
+
+def _check(st: int, what: str):
+    if st != 0:
+        raise SqmiError(f"{what}: {lib().sq_status_string(st).decode()} (status {st})")
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float16:
+        return F16
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"16-bit floating tensor expected, got {t.dtype}")
+
+
+def _dev(t: torch.Tensor, dtype=None, name="tensor"):
+    if not t.is_cuda:
+        raise SqmiError(f"{name} must be a GPU tensor")
+    if not t.is_contiguous():
+        raise SqmiError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _opt(t, dtype, name):
+    return None if t is None else _dev(t, dtype, name)
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def workspace_bytes(op: int, t: int, c_i: int, c_o: int) -> int:
+    return int(lib().sq_workspace_bytes(op, t, c_i, c_o))
+
+
+def _workspace(nbytes: int, device, workspace):
+    if nbytes == 0 and workspace is None:
+        return None, 0, None
+    if workspace is None:
+        workspace = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
+    elif workspace.numel() * workspace.element_size() < nbytes:
+        raise SqmiError("workspace too small")
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size(), workspace
+
+
+def smooth_scales(x_absmax: torch.Tensor, w_absmax: torch.Tensor, alpha: float):
+    """Eq. 4 on HOST fp32 tensors -> (s, inv_s) host fp32 tensors."""
+    xa = x_absmax.detach().to("cpu", torch.float32).contiguous()
+    wa = w_absmax.detach().to("cpu", torch.float32).contiguous()
+    s = torch.empty_like(xa)
+    inv_s = torch.empty_like(xa)
+    _check(lib().sq_smooth_scales(xa.data_ptr(), wa.data_ptr(), alpha, xa.numel(), s.data_ptr(), inv_s.data_ptr()),
+           "sq_smooth_scales")
+    return s, inv_s
+
+
+def act_absmax_per_channel(x: torch.Tensor) -> torch.Tensor:
+    t, c_i = x.shape
+    out = torch.empty(c_i, dtype=torch.float32, device=x.device)
+    _check(lib().sq_act_absmax_per_channel(_dev(x, None, "x"), _dt(x), t, c_i, out.data_ptr(), _stream()),
+           "sq_act_absmax_per_channel")
+    return out
+
+
+def weight_absmax_per_in_channel(w: torch.Tensor) -> torch.Tensor:
+    c_i, c_o = w.shape
+    out = torch.empty(c_i, dtype=torch.float32, device=w.device)
+    _check(lib().sq_weight_absmax_per_in_channel(_dev(w, None, "w"), _dt(w), c_i, c_o, out.data_ptr(), _stream()),
+           "sq_weight_absmax_per_in_channel")
+    return out
+
+
+def prepare_weight(w: torch.Tensor, s: torch.Tensor | None = None, workspace=None):
+    """W [c_i, c_o] (+ optional device fp32 s [c_i]) -> (wq int8 [c_o, c_i], w_scale fp32 [1])."""
+    c_i, c_o = w.shape
+    wq = torch.empty((c_o, c_i), dtype=torch.int8, device=w.device)
+    w_scale = torch.empty(1, dtype=torch.float32, device=w.device)
+    wp, wb, keep = _workspace(workspace_bytes(OP_PREPARE_WEIGHT, 0, c_i, c_o), w.device, workspace)
+    _check(lib().sq_prepare_weight(_dev(w, None, "w"), _dt(w), _opt(s, torch.float32, "s"), c_i, c_o, wq.data_ptr(),
+                                   w_scale.data_ptr(), wp, wb, _stream()), "sq_prepare_weight")
+    return wq, w_scale
+
+
+def quantize_act(x: torch.Tensor, mode: int, inv_s: torch.Tensor | None = None, static_scale: torch.Tensor | None = None,
+                 c_i: int | None = None, out=None, workspace=None):
+    """x [t, ldx] -> (xq int8 [t, c_i], scale fp32 [t] or [1]).  ``c_i`` < ldx quantizes a column prefix."""
+    t, ldx = x.shape
+    c_i = ldx if c_i is None else c_i
+    if out is None:
+        xq = torch.empty((t, c_i), dtype=torch.int8, device=x.device)
+        if mode == PER_TENSOR_STATIC:
+            if static_scale is None:
+                raise SqmiError("static mode needs static_scale")
+            scale = static_scale
+        else:
+            scale = torch.empty(t if mode == PER_TOKEN_DYNAMIC else 1, dtype=torch.float32, device=x.device)
+    else:
+        xq, scale = out
+    wp, wb, keep = _workspace(workspace_bytes(OP_QUANTIZE_ACT, t, c_i, 0) if mode == PER_TENSOR_DYNAMIC else 0,
+                              x.device, workspace)
+    _check(lib().sq_quantize_act(_dev(x, None, "x"), _dt(x), t, c_i, ldx, _opt(inv_s, torch.float32, "inv_s"), mode,
+                                 _dev(scale, torch.float32, "scale"), _dev(xq, torch.int8, "xq"), wp, wb, _stream()),
+           "sq_quantize_act")
+    return xq, scale
+
+
+def w8a8_linear(xq: torch.Tensor, x_scale: torch.Tensor, wq: torch.Tensor, w_scale: torch.Tensor, out_dtype,
+                bias=None, residual=None, relu: bool = False, out=None, workspace=None) -> torch.Tensor:
+    t, c_i = xq.shape
+    c_o = wq.shape[0]
+    if wq.shape[1] != c_i:
+        raise SqmiError("wq must be [c_o, c_i]")
+    if x_scale.numel() not in (1, t):
+        raise SqmiError("x_scale must have 1 or t entries")
+    y = torch.empty((t, c_o), dtype=out_dtype, device=xq.device) if out is None else out
+    wp, wb, keep = _workspace(workspace_bytes(OP_W8A8_LINEAR, t, c_i, c_o), xq.device, workspace)
+    per_token = int(x_scale.numel() == t)
+    _check(lib().sq_w8a8_linear(_dev(xq, torch.int8, "xq"), _dev(x_scale, torch.float32, "x_scale"), per_token,
+                                _dev(wq, torch.int8, "wq"), _dev(w_scale, torch.float32, "w_scale"),
+                                _opt(bias, torch.float32, "bias"), _opt(residual, out_dtype, "residual"), int(relu),
+                                _dev(y, out_dtype, "y"), _dt(y), t, c_i, c_o, wp, wb, _stream()), "sq_w8a8_linear")
+    return y
+
+
+def i8_gemm_i32(xq: torch.Tensor, wq: torch.Tensor, workspace=None) -> torch.Tensor:
+    t, c_i = xq.shape
+    c_o = wq.shape[0]
+    acc = torch.empty((t, c_o), dtype=torch.int32, device=xq.device)
+    wp, wb, keep = _workspace(workspace_bytes(OP_I8_GEMM_I32, t, c_i, c_o), xq.device, workspace)
+    _check(lib().sq_i8_gemm_i32(_dev(xq, torch.int8, "xq"), _dev(wq, torch.int8, "wq"), acc.data_ptr(), t, c_i, c_o,
+                                wp, wb, _stream()), "sq_i8_gemm_i32")
+    return acc
+
+
+def w8a8_bmm(a: torch.Tensor, bm: torch.Tensor, trans_b: bool, alpha: float, out_dtype, out=None) -> torch.Tensor:
+    """a [b, m, k]; bm [b, n, k] if trans_b else [b, k, n] -> c [b, m, n]."""
+    b, m, k = a.shape
+    n = bm.shape[1] if trans_b else bm.shape[2]
+    c = torch.empty((b, m, n), dtype=out_dtype, device=a.device) if out is None else out
+    _check(lib().sq_w8a8_bmm(_dev(a, torch.int8, "a"), _dev(bm, torch.int8, "bm"), int(trans_b), alpha,
+                             _dev(c, out_dtype, "c"), _dt(c), b, m, n, k, m * k, n * k, m * n, _stream()), "sq_w8a8_bmm")
+    return c
+
+
+def softmax_quant_p(s: torch.Tensor, out=None) -> torch.Tensor:
+    cols = s.shape[-1]
+    rows = s.numel() // cols
+    pq = torch.empty(s.shape, dtype=torch.int8, device=s.device) if out is None else out
+    _check(lib().sq_softmax_quant_p(_dev(s, None, "s"), _dt(s), rows, cols, _dev(pq, torch.int8, "pq"), _stream()),
+           "sq_softmax_quant_p")
+    return pq
+
+
+def ln_quantize(x: torch.Tensor, gamma_f: torch.Tensor, beta_f: torch.Tensor, eps: float = 1e-5, out=None):
+    t, c_i = x.shape
+    if out is None:
+        xq = torch.empty((t, c_i), dtype=torch.int8, device=x.device)
+        scale = torch.empty(t, dtype=torch.float32, device=x.device)
+    else:
+        xq, scale = out
+    _check(lib().sq_ln_quantize(_dev(x, None, "x"), _dt(x), t, c_i, _dev(gamma_f, torch.float32, "gamma_f"),
+                                _dev(beta_f, torch.float32, "beta_f"), eps, _dev(scale, torch.float32, "scale"),
+                                _dev(xq, torch.int8, "xq"), _stream()), "sq_ln_quantize")
+    return xq, scale

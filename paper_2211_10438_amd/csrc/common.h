@@ -1,0 +1,63 @@
+// Shared host/device helpers of the sqmi HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sqmi.h"
+
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
+
+#define SQ_DEVICE static __device__ __forceinline__
+
+// ---- 16-bit formats.  fp16 uses the hardware converts (round-to-nearest-even in the default
+// mode); bf16 is widened by a shift and narrowed with the integer nearest-even rule.
+SQ_DEVICE float f16_bits_to_f32(uint32_t h) { return (float)__builtin_bit_cast(_Float16, (uint16_t)h); }
+SQ_DEVICE float bf16_bits_to_f32(uint32_t b) { return __builtin_bit_cast(float, b << 16); }
+SQ_DEVICE uint32_t f32_to_f16_bits(float v) { return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)v); }
+SQ_DEVICE uint32_t f32_to_bf16_bits(float v)
+{
+    uint32_t u = __builtin_bit_cast(uint32_t, v);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+template <bool BF16> SQ_DEVICE float load16_bits(uint32_t bits)
+{
+    return BF16 ? bf16_bits_to_f32(bits & 0xffffu) : f16_bits_to_f32(bits & 0xffffu);
+}
+template <bool BF16> SQ_DEVICE uint32_t store16_bits(float v)
+{
+    return BF16 ? f32_to_bf16_bits(v) : f32_to_f16_bits(v);
+}
+
+// Eq. 1 rounding and range: round-half-even of v, saturated to [-127, 127], as an int.
+SQ_DEVICE int round_code(float v)
+{
+    float r = __builtin_rintf(v);
+    r = __builtin_fminf(__builtin_fmaxf(r, -127.0f), 127.0f);
+    return (int)r;
+}
+
+// Wave-wide max over 64 lanes (all lanes receive the result).
+SQ_DEVICE float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = __builtin_fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+SQ_DEVICE float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// ---- host side
+static inline bool sq_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static inline sq_status sq_launch_status()
+{
+    return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_HIP;
+}

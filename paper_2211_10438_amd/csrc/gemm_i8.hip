@@ -1,0 +1,483 @@
+// INT8 x INT8 -> INT32 MFMA GEMM / batched GEMM for gfx950 with a fused dequantizing epilogue.
+//
+// Computes the integer contraction of Eq. 2, acc[m, n] = sum_k A[m, k] * B[n, k] (both operands
+// K-contiguous: activations [T, C_i], prepared weights [C_o, C_i]), and applies the outer-dimension
+// scaling of Eq. 2 (per-token Delta_X times Delta_W, optional bias / ReLU / residual) to the int32
+// accumulators while they are still in registers.
+//
+// Design (CDNA4):
+//  * v_mfma_i32_32x32x32_i8, one wave owns a (MI*32) x (NI*32) block of accumulators.
+//  * Operand tiles travel HBM -> LDS with global_load_lds_dwordx4 (no VGPR staging), NSTAGE deep.
+//    LDS holds a tile as 16-row blocks; inside a block the 16-byte K-chunks are stored
+//    [chunk][row], so (a) one wave-wide load instruction fills 1 KB contiguous LDS from 16 rows x
+//    64 contiguous bytes of global memory and (b) every 16-lane group of an MFMA operand read
+//    (ds_read_b128) touches 256 contiguous bytes: no bank conflicts by construction.
+//  * One s_barrier per 64-wide K step; operand fragments are double buffered in registers so the
+//    LDS reads of the next half step are in flight while the MFMAs of this half step issue.
+//  * Tiles are enumerated XCD-aware: the workgroups an XCD runs concurrently cover a compact
+//    block of output tiles, so its L2 serves the shared A rows / B rows.
+//  * Optional split-K writes int32 partial tiles to a workspace, reduced (exactly, int32) by a
+//    second small kernel that also runs the epilogue.
+#include "common.h"
+
+#define GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+namespace {
+
+enum { EPI_DEQUANT = 0, EPI_I32 = 1 };
+
+struct GemmArgs {
+    const int8_t* A;  // [batch][M, K], row stride lda bytes
+    const int8_t* B;  // [batch][N, K], row stride ldb bytes
+    int M, N, K;
+    int64_t lda, ldb;
+    int64_t strideA, strideB, strideC;  // batch strides in elements
+    int tiles_m, tiles_n, splits, iters_per_split;
+    // dequant epilogue
+    void* C;  // [batch][M, N] 16-bit, row stride N
+    const float* x_scale;  // [M] or [1] or NULL (then `alpha` is the whole scale)
+    int per_token;
+    const float* w_scale;  // [1]
+    float alpha;
+    const float* bias;     // [N] or NULL
+    const void* residual;  // [M, N] out dtype or NULL
+    int relu;
+    // int32 output (raw accumulators or split-K partials): [splits][M, N]
+    int32_t* acc_out;
+};
+
+template <int N> SQ_DEVICE void wait_vmcnt_imm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+// Wait until at most min(m, MAXM) pipeline stages (LPS loads each, issued by this wave) are still
+// in flight.  s_waitcnt takes an immediate, hence the compile-time ladder.
+template <int LPS, int MAXM> SQ_DEVICE void wait_stages(int m)
+{
+    if constexpr (MAXM <= 0) {
+        wait_vmcnt_imm<0>();
+    } else {
+        if (m >= MAXM) wait_vmcnt_imm<MAXM * LPS>();
+        else wait_stages<LPS, MAXM - 1>(m);
+    }
+}
+
+template <bool BF16>
+SQ_DEVICE uint32_t dequant_one(int acc, float c, float bias, bool has_bias, bool relu, uint32_t res_bits, bool has_res)
+{
+    float v = (float)acc * c;
+    if (has_bias) v = v + bias;
+    if (relu) v = v > 0.0f ? v : 0.0f;
+    if (has_res) v = v + load16_bits<BF16>(res_bits);
+    return store16_bits<BF16>(v);
+}
+
+// BM x BN output tile per workgroup, WGM x WGN waves, BK = 64 bytes of K per pipeline stage.
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, int EPI, bool BF16>
+__global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArgs p)
+{
+    constexpr int NW = WGM * WGN, BK = 64;
+    constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
+    constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE = A_BYTES + B_BYTES;
+    constexpr int RBA = BM / 16, RBB = BN / 16;  // 16-row blocks per operand tile
+    constexpr int SA = (RBA + NW - 1) / NW, SB = (RBB + NW - 1) / NW, LPS = SA + SB;
+    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
+    static_assert(NSTAGE >= 3 && (NSTAGE - 2) * LPS <= 63, "pipeline depth exceeds the 6-bit vmcnt");
+    static_assert(NSTAGE * STAGE <= 160 * 1024, "LDS budget");
+    __shared__ __attribute__((aligned(1024))) char smem[NSTAGE * STAGE];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave / WGN, wn = wave % WGN;
+
+    // ---- which tile: hardware deals consecutive workgroup ids round-robin to the 8 XCDs; give
+    // each XCD a contiguous range of the logical order, and make that order walk groups of 8
+    // m-tiles column by column so that concurrently running tiles share operand rows in L2.
+    const int total = gridDim.x;
+    int pid;
+    {
+        const int wg = blockIdx.x, xcd = wg & 7, j = wg >> 3;
+        const int q = total >> 3, r = total & 7;
+        pid = xcd * q + (xcd < r ? xcd : r) + j;
+    }
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int split = pid / tiles;
+    int tm, tn;
+    {
+        const int t = pid - split * tiles;
+        constexpr int GM = 8;
+        const int per_group = GM * p.tiles_n;
+        const int g = t / per_group, first_m = g * GM;
+        const int gsz = (p.tiles_m - first_m) < GM ? (p.tiles_m - first_m) : GM;
+        const int in = t - g * per_group;
+        tm = first_m + in % gsz;
+        tn = in / gsz;
+    }
+    const int batch = blockIdx.y;
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int nk_total = (p.K + BK - 1) / BK;
+    const int kbeg = split * p.iters_per_split;
+    const int nk = (nk_total - kbeg) < p.iters_per_split ? (nk_total - kbeg) : p.iters_per_split;
+    const int tail_chunks = (p.K & (BK - 1)) >> 4;  // valid 16-byte chunks of the last K step (0 = all 4)
+
+    const int8_t* Ab = p.A + (int64_t)batch * p.strideA + (int64_t)m0 * p.lda + (int64_t)kbeg * BK;
+    const int8_t* Bb = p.B + (int64_t)batch * p.strideB + (int64_t)n0 * p.ldb + (int64_t)kbeg * BK;
+
+    // ---- global -> LDS load slots of this wave.  Slot i moves 16-row block (i*NW + wave); lane l
+    // fetches row (l & 15), chunk (l >> 4) and lands at LDS byte l*16 of the block's 1 KB.
+    const int chunk = lane >> 4;
+    uint32_t offA[SA], offB[SB];
+    int ldsA[SA], ldsB[SB];
+#pragma unroll
+    for (int i = 0; i < SA; ++i) {
+        const int rb = (i * NW + wave) % RBA;  // wraps only when RBA is not a multiple of NW: a benign duplicate
+        int row = rb * 16 + (lane & 15);
+        const int last = p.M - 1 - m0;
+        row = row < last ? row : last;
+        offA[i] = (uint32_t)(row * (int)p.lda + chunk * 16);
+        ldsA[i] = rb * 1024;
+    }
+#pragma unroll
+    for (int i = 0; i < SB; ++i) {
+        const int rb = (i * NW + wave) % RBB;
+        int row = rb * 16 + (lane & 15);
+        const int last = p.N - 1 - n0;
+        row = row < last ? row : last;
+        offB[i] = (uint32_t)(row * (int)p.ldb + chunk * 16);
+        ldsB[i] = A_BYTES + rb * 1024;
+    }
+
+    // K tail (K % 64 != 0 happens only in the globally last K step): lanes whose chunk lies beyond K
+    // re-read chunk 0 (valid memory); their A fragments are zeroed in registers before the MFMAs.
+    const bool has_tail = tail_chunks != 0 && (kbeg + nk == nk_total);
+    auto issue_stage = [&](int kt, int buf) {
+        const int8_t* a = Ab + (int64_t)kt * BK;
+        const int8_t* b = Bb + (int64_t)kt * BK;
+        char* base = smem + buf * STAGE;
+        const uint32_t back = (has_tail && kt == nk - 1 && chunk >= tail_chunks) ? (uint32_t)chunk * 16u : 0u;
+#pragma unroll
+        for (int i = 0; i < SA; ++i)
+            __builtin_amdgcn_global_load_lds(GPTR(a + (offA[i] - back)), LPTR(base + ldsA[i]), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < SB; ++i)
+            __builtin_amdgcn_global_load_lds(GPTR(b + (offB[i] - back)), LPTR(base + ldsB[i]), 16, 0, 0);
+    };
+
+    // ---- MFMA operand fragments.  For the 32x32x32 MFMA lane l feeds row (l & 31) with the 16
+    // bytes of K-chunk (l >> 5) of the 32-wide K step.
+    const int lane_off = ((lane & 31) >> 4) * 1024 + (lane >> 5) * 256 + (lane & 15) * 16;
+    const int fragA0 = wm * (WM / 16) * 1024 + lane_off;
+    const int fragB0 = A_BYTES + wn * (WN / 16) * 1024 + lane_off;
+
+    v4i fa0[MI], fb0[NI], fa1[MI], fb1[NI];
+    v16i acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+
+    auto read_frags = [&](v4i(&fa)[MI], v4i(&fb)[NI], int buf, int kk) {
+        const char* sa = smem + buf * STAGE + fragA0 + kk * 512;
+        const char* sb = smem + buf * STAGE + fragB0 + kk * 512;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) fa[i] = *(const v4i*)(sa + i * 2048);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) fb[j] = *(const v4i*)(sb + j * 2048);
+    };
+    auto mfma_all = [&](const v4i(&fa)[MI], const v4i(&fb)[NI]) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    };
+    // Scheduling hint for one half step (MI+NI fragment reads of the next half, MI*NI MFMAs of this
+    // one): interleave the LDS reads with the MFMAs so the four waves of the workgroup do not hit
+    // the LDS pipe in one burst.
+    auto interleave_hint = [&]() {
+        // one MFMA, one DS read, ...; the MFMAs left over close the half step, which gives the last
+        // read time to land before the next half step waits for it.
+        constexpr int READS = MI + NI, MFMAS = MI * NI;
+#pragma unroll
+        for (int r = 0; r < READS; ++r) {
+            if (r < MFMAS) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        if (MFMAS > READS) __builtin_amdgcn_sched_group_barrier(0x008, MFMAS - READS, 0);
+    };
+
+    // ---- pipeline prologue: stages 0 .. NSTAGE-2 in flight, stage 0 landed, first fragments read.
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; ++s)
+        if (s < nk) issue_stage(s, s);
+    {
+        const int inflight = nk < NSTAGE - 1 ? nk : NSTAGE - 1;
+        wait_stages<LPS, NSTAGE - 2>(inflight - 1);
+    }
+    __builtin_amdgcn_s_barrier();
+    read_frags(fa0, fb0, 0, 0);
+
+    // Steady state: every K step but the last.  No LDS access is conditional here, so the compiler
+    // can wait on exactly the fragment reads an MFMA group needs.
+    int buf = 0;
+    for (int it = 0; it < nk - 1; ++it) {
+        // first half of K step `it`
+        read_frags(fa1, fb1, buf, 1);
+        mfma_all(fa0, fb0);
+        interleave_hint();
+        // second half; meanwhile make stage it+1 visible and refill the buffer freed by step it-1
+        const int nbuf = buf + 1 == NSTAGE ? 0 : buf + 1;
+        int last = it + NSTAGE - 2;
+        last = last < nk - 1 ? last : nk - 1;
+        wait_stages<LPS, NSTAGE - 3>(last - (it + 1));
+        __builtin_amdgcn_s_barrier();
+        if (it + NSTAGE - 1 < nk) issue_stage(it + NSTAGE - 1, buf == 0 ? NSTAGE - 1 : buf - 1);
+        read_frags(fa0, fb0, nbuf, 0);
+        mfma_all(fa1, fb1);
+        interleave_hint();
+        buf = nbuf;
+    }
+    // last K step
+    read_frags(fa1, fb1, buf, 1);
+    if (has_tail) {
+        // chunk index of this lane inside the 64-byte step: kk*2 + (lane >> 5)
+        const int c0 = lane >> 5, c1 = 2 + (lane >> 5);
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            if (c0 >= tail_chunks) fa0[i] = v4i{0, 0, 0, 0};
+            if (c1 >= tail_chunks) fa1[i] = v4i{0, 0, 0, 0};
+        }
+    }
+    mfma_all(fa0, fb0);
+    mfma_all(fa1, fb1);
+
+    // ---- epilogue.  32x32 accumulator layout: lane l, register v holds
+    // row 8*(v/4) + 4*(l>>5) + (v&3), column (l & 31).
+    const int col_l = lane & 31, row_l = (lane >> 5) * 4;
+    if constexpr (EPI == EPI_I32) {
+        int32_t* out = p.acc_out + ((int64_t)split * p.M) * p.N;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = m0 + wm * WM + i * 32 + 8 * (v >> 2) + row_l + (v & 3);
+                if (row < p.M) {
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) {
+                        const int col = n0 + wn * WN + j * 32 + col_l;
+                        if (col < p.N) out[(int64_t)row * p.N + col] = acc[i][j][v];
+                    }
+                }
+            }
+    } else {
+        uint16_t* C = (uint16_t*)p.C + (int64_t)batch * p.strideC;
+        const uint16_t* R = (const uint16_t*)p.residual;
+        const float ws = p.x_scale ? p.w_scale[0] : 0.0f;
+        const float xs0 = (p.x_scale && !p.per_token) ? p.x_scale[0] : 0.0f;
+        float bj[NI];
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int col = n0 + wn * WN + j * 32 + col_l;
+            bj[j] = (p.bias && col < p.N) ? p.bias[col] : 0.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = m0 + wm * WM + i * 32 + 8 * (v >> 2) + row_l + (v & 3);
+                if (row < p.M) {
+                    float c;
+                    if (p.x_scale) c = (p.per_token ? p.x_scale[row] : xs0) * ws;
+                    else c = p.alpha;
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) {
+                        const int col = n0 + wn * WN + j * 32 + col_l;
+                        if (col < p.N) {
+                            const int64_t idx = (int64_t)row * p.N + col;
+                            const uint32_t rb = R ? R[idx] : 0u;
+                            C[idx] = (uint16_t)dequant_one<BF16>(acc[i][j][v], c, bj[j], p.bias != nullptr, p.relu != 0,
+                                                                 rb, R != nullptr);
+                        }
+                    }
+                }
+            }
+    }
+}
+
+// Split-K reduction: sums the int32 partial tiles (exact) and applies the same epilogue.
+template <bool BF16>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs p, int to_i32)
+{
+    const int64_t total = (int64_t)p.M * p.N;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * blockDim.x) {
+        int sum = 0;
+        for (int s = 0; s < p.splits; ++s) sum += p.acc_out[(int64_t)s * total + idx];
+        const int row = (int)(idx / p.N), col = (int)(idx - (int64_t)row * p.N);
+        if (to_i32) {
+            ((int32_t*)p.C)[idx] = sum;
+        } else {
+            float c;
+            if (p.x_scale) c = (p.per_token ? p.x_scale[row] : p.x_scale[0]) * p.w_scale[0];
+            else c = p.alpha;
+            const uint16_t* R = (const uint16_t*)p.residual;
+            ((uint16_t*)p.C)[idx] = (uint16_t)dequant_one<BF16>(sum, c, p.bias ? p.bias[col] : 0.0f, p.bias != nullptr,
+                                                                p.relu != 0, R ? R[idx] : 0u, R != nullptr);
+        }
+    }
+}
+
+// ---------------------------------------------------------------- host side: tile / split choice
+
+struct Plan {
+    int cfg;     // 0: 256x256 (prefill)  1: 128x256  2: 64x256  3: 32x256
+    int bm, bn;
+    int splits, iters_per_split;
+    int tiles_m, tiles_n;
+};
+
+constexpr int kNumCU = 256;
+
+Plan make_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split)
+{
+    Plan pl{};
+    if (M > 128) { pl.cfg = 0; pl.bm = 256; }
+    else if (M > 64) { pl.cfg = 1; pl.bm = 128; }
+    else if (M > 32) { pl.cfg = 2; pl.bm = 64; }
+    else { pl.cfg = 3; pl.bm = 32; }
+    pl.bn = 256;
+    pl.tiles_m = (int)((M + pl.bm - 1) / pl.bm);
+    pl.tiles_n = (int)((N + pl.bn - 1) / pl.bn);
+    const int nk = (int)((K + 63) / 64);
+    int splits = 1;
+    if (allow_split && batch == 1) {
+        const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
+        // Weight-streaming shapes: a few workgroups per CU keep every HBM channel busy.
+        // Compute-bound shapes: split only to fill the last partial round of tiles.
+        const int64_t want = pl.cfg == 0 ? kNumCU : 2 * kNumCU;
+        if (tiles < want) {
+            splits = (int)((want + tiles - 1) / tiles);
+            const int max_splits = nk / 8 > 0 ? nk / 8 : 1;  // at least 8 K steps per split
+            if (splits > max_splits) splits = max_splits;
+            if (splits > 32) splits = 32;
+        }
+    }
+    int per = (nk + splits - 1) / splits;
+    splits = (nk + per - 1) / per;  // no empty split
+    pl.splits = splits;
+    pl.iters_per_split = per;
+    return pl;
+}
+
+template <int EPI, bool BF16>
+void launch_cfg(const Plan& pl, const GemmArgs& a, int batch, hipStream_t st)
+{
+    dim3 grid((unsigned)(pl.tiles_m * pl.tiles_n * pl.splits), (unsigned)batch);
+    switch (pl.cfg) {
+        case 0: hipLaunchKernelGGL((gemm_i8_kernel<256, 256, 2, 2, 4, EPI, BF16>), grid, dim3(256), 0, st, a); break;
+        case 1: hipLaunchKernelGGL((gemm_i8_kernel<128, 256, 1, 4, 6, EPI, BF16>), grid, dim3(256), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((gemm_i8_kernel<64, 256, 1, 4, 7, EPI, BF16>), grid, dim3(256), 0, st, a); break;
+        default: hipLaunchKernelGGL((gemm_i8_kernel<32, 256, 1, 4, 8, EPI, BF16>), grid, dim3(256), 0, st, a); break;
+    }
+}
+
+sq_status run_gemm(GemmArgs a, int64_t batch, bool to_i32, bool bf16, void* workspace, size_t ws_bytes, hipStream_t st)
+{
+    Plan pl = make_plan(a.M, a.N, a.K, batch, true);
+    a.tiles_m = pl.tiles_m;
+    a.tiles_n = pl.tiles_n;
+    a.splits = pl.splits;
+    a.iters_per_split = pl.iters_per_split;
+    if (pl.splits > 1) {
+        const size_t need = (size_t)pl.splits * a.M * a.N * sizeof(int32_t);
+        if (!workspace || ws_bytes < need) return SQ_ERR_WORKSPACE;
+        void* final_out = to_i32 ? (void*)a.acc_out : a.C;
+        a.acc_out = (int32_t*)workspace;
+        launch_cfg<EPI_I32, false>(pl, a, 1, st);
+        a.C = final_out;
+        const int64_t total = (int64_t)a.M * a.N;
+        int blocks = (int)((total + 255) / 256);
+        if (blocks > 4096) blocks = 4096;
+        if (bf16) hipLaunchKernelGGL(splitk_reduce_kernel<true>, dim3(blocks), dim3(256), 0, st, a, to_i32 ? 1 : 0);
+        else hipLaunchKernelGGL(splitk_reduce_kernel<false>, dim3(blocks), dim3(256), 0, st, a, to_i32 ? 1 : 0);
+    } else if (to_i32) {
+        launch_cfg<EPI_I32, false>(pl, a, (int)batch, st);
+    } else if (bf16) {
+        launch_cfg<EPI_DEQUANT, true>(pl, a, (int)batch, st);
+    } else {
+        launch_cfg<EPI_DEQUANT, false>(pl, a, (int)batch, st);
+    }
+    return sq_launch_status();
+}
+
+bool dims_ok(int64_t t, int64_t c_i, int64_t c_o)
+{
+    const int64_t lim = (int64_t)1 << 31;
+    return t > 0 && c_i > 0 && c_o > 0 && t < lim && c_i < lim && c_o < lim && t * c_o < ((int64_t)1 << 40) &&
+           256 * c_i < lim;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t sq_gemm_workspace_bytes(int64_t t, int64_t c_i, int64_t c_o)
+{
+    if (!dims_ok(t, c_i, c_o)) return 0;
+    Plan pl = make_plan(t, c_o, c_i, 1, true);
+    return pl.splits > 1 ? (size_t)pl.splits * t * c_o * sizeof(int32_t) : 0;
+}
+
+sq_status sq_w8a8_linear(const int8_t* xq, const float* x_scale, int x_scale_per_token, const int8_t* wq,
+                         const float* w_scale, const float* bias, const void* residual, int relu, void* y,
+                         sq_dtype out, int64_t t, int64_t c_i, int64_t c_o, void* workspace, size_t ws_bytes,
+                         void* stream)
+{
+    if (!xq || !x_scale || !wq || !w_scale || !y) return SQ_ERR_NULL;
+    if (!dims_ok(t, c_i, c_o)) return SQ_ERR_SHAPE;
+    if (out != SQ_F16 && out != SQ_BF16) return SQ_ERR_UNSUPPORTED;
+    if ((c_i & 15) || !sq_aligned16(xq) || !sq_aligned16(wq) || !sq_aligned16(y) ||
+        (residual && !sq_aligned16(residual)) || (workspace && !sq_aligned16(workspace)))
+        return SQ_ERR_ALIGN;
+    GemmArgs a{};
+    a.A = xq; a.B = wq;
+    a.M = (int)t; a.N = (int)c_o; a.K = (int)c_i;
+    a.lda = c_i; a.ldb = c_i;
+    a.C = y; a.x_scale = x_scale; a.per_token = x_scale_per_token ? 1 : 0; a.w_scale = w_scale;
+    a.bias = bias; a.residual = residual; a.relu = relu ? 1 : 0;
+    return run_gemm(a, 1, false, out == SQ_BF16, workspace, ws_bytes, (hipStream_t)stream);
+}
+
+sq_status sq_i8_gemm_i32(const int8_t* xq, const int8_t* wq, int32_t* acc, int64_t t, int64_t c_i, int64_t c_o,
+                         void* workspace, size_t ws_bytes, void* stream)
+{
+    if (!xq || !wq || !acc) return SQ_ERR_NULL;
+    if (!dims_ok(t, c_i, c_o)) return SQ_ERR_SHAPE;
+    if ((c_i & 15) || !sq_aligned16(xq) || !sq_aligned16(wq) || !sq_aligned16(acc) ||
+        (workspace && !sq_aligned16(workspace)))
+        return SQ_ERR_ALIGN;
+    GemmArgs a{};
+    a.A = xq; a.B = wq;
+    a.M = (int)t; a.N = (int)c_o; a.K = (int)c_i;
+    a.lda = c_i; a.ldb = c_i;
+    a.acc_out = acc;
+    a.C = acc;
+    return run_gemm(a, 1, true, false, workspace, ws_bytes, (hipStream_t)stream);
+}
+
+// Attention BMM dispatcher behind sq_w8a8_bmm (arguments already validated).
+sq_status sq_internal_bmm(const int8_t* a_, const int8_t* b_, int trans_b, float alpha, void* c, sq_dtype out,
+                          int64_t batch, int64_t m, int64_t n, int64_t k, int64_t stride_a, int64_t stride_b,
+                          int64_t stride_c, void* stream)
+{
+    if (!trans_b) return SQ_ERR_UNSUPPORTED;
+    GemmArgs a{};
+    a.A = a_; a.B = b_;
+    a.M = (int)m; a.N = (int)n; a.K = (int)k;
+    a.lda = k; a.ldb = k;
+    a.strideA = stride_a; a.strideB = stride_b; a.strideC = stride_c;
+    a.C = c; a.alpha = alpha;
+    return run_gemm(a, batch, false, out == SQ_BF16, nullptr, 0, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,340 @@
+// Activation quantization (Eq. 1) at the granularities of Table 2, gfx950.
+//
+// Per-token dynamic (O1): one pass over HBM.  A row lives in registers between the absmax
+// reduction and the rounding, so the traffic is 2 B read + 1 B written per element.  Rows are
+// handled by a 256-thread workgroup (wide rows) or by one 64-lane wave (narrow rows, reduction
+// with cross-lane shuffles only).
+// Per-tensor static (O3): pure elementwise pass, saturating.
+// Per-tensor dynamic (O2): an absmax pass (atomic max on the bit pattern of a non-negative float)
+// followed by the elementwise pass.
+#include "common.h"
+
+namespace {
+
+template <bool BF16> SQ_DEVICE void unpack8(const v4u raw, float (&f)[8])
+{
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        f[2 * e] = load16_bits<BF16>(raw[e]);
+        f[2 * e + 1] = load16_bits<BF16>(raw[e] >> 16);
+    }
+}
+
+// x_hat = fl32(x * inv_s_j) for the 8 channels starting at `col` (Eq. 3 applied to the activation).
+SQ_DEVICE void smooth8(float (&f)[8], const float* inv_s, int col)
+{
+    const float4 a = *(const float4*)(inv_s + col);
+    const float4 b = *(const float4*)(inv_s + col + 4);
+    f[0] = f[0] * a.x; f[1] = f[1] * a.y; f[2] = f[2] * a.z; f[3] = f[3] * a.w;
+    f[4] = f[4] * b.x; f[5] = f[5] * b.y; f[6] = f[6] * b.z; f[7] = f[7] * b.w;
+}
+
+SQ_DEVICE float absmax8(const float (&f)[8])
+{
+    float m = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) m = __builtin_fmaxf(m, __builtin_fabsf(f[e]));
+    return m;
+}
+
+SQ_DEVICE v2u quant8(const float (&f)[8], float r)
+{
+    v2u out;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w |= ((uint32_t)round_code(f[4 * h + e] * r) & 0xffu) << (8 * e);
+        out[h] = w;
+    }
+    return out;
+}
+
+// Block-wide max for a 256-thread workgroup.
+SQ_DEVICE float block_max_256(float v, float* red)
+{
+    v = wave_max(v);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return __builtin_fmaxf(__builtin_fmaxf(red[0], red[1]), __builtin_fmaxf(red[2], red[3]));
+}
+
+// One row per 256-thread workgroup; NV 16-byte vectors (8 elements) per thread kept in registers.
+template <bool BF16, int NV>
+__global__ __launch_bounds__(256) void quant_per_token_block(const uint16_t* __restrict__ x, int64_t ldx, int c_i,
+                                                            const float* __restrict__ inv_s, float* __restrict__ scale,
+                                                            int8_t* __restrict__ xq)
+{
+    __shared__ float red[4];
+    const int64_t row = blockIdx.x;
+    const v4u* xr = (const v4u*)(x + row * ldx);
+    const int nvec = c_i >> 3;
+    v4u raw[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = threadIdx.x + i * 256;
+        raw[i] = idx < nvec ? __builtin_nontemporal_load(xr + idx) : v4u{0, 0, 0, 0};
+    }
+    float m = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = threadIdx.x + i * 256;
+        float f[8];
+        unpack8<BF16>(raw[i], f);
+        if (inv_s && idx < nvec) smooth8(f, inv_s, idx * 8);
+        m = __builtin_fmaxf(m, absmax8(f));
+    }
+    const float a = block_max_256(m, red);
+    const float r = a > 0.0f ? 127.0f / a : 0.0f;
+    if (threadIdx.x == 0) scale[row] = a / 127.0f;
+    v2u* out = (v2u*)(xq + row * (int64_t)c_i);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = threadIdx.x + i * 256;
+        if (idx < nvec) {
+            float f[8];
+            unpack8<BF16>(raw[i], f);
+            if (inv_s) smooth8(f, inv_s, idx * 8);
+            __builtin_nontemporal_store(quant8(f, r), out + idx);
+        }
+    }
+}
+
+// One row per wave (4 rows per workgroup): for narrow rows.
+template <bool BF16, int NV>
+__global__ __launch_bounds__(256) void quant_per_token_wave(const uint16_t* __restrict__ x, int64_t ldx, int c_i, int64_t t,
+                                                           const float* __restrict__ inv_s, float* __restrict__ scale,
+                                                           int8_t* __restrict__ xq)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= t) return;
+    const v4u* xr = (const v4u*)(x + row * ldx);
+    const int nvec = c_i >> 3;
+    v4u raw[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = lane + i * 64;
+        raw[i] = idx < nvec ? xr[idx] : v4u{0, 0, 0, 0};
+    }
+    float m = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = lane + i * 64;
+        float f[8];
+        unpack8<BF16>(raw[i], f);
+        if (inv_s && idx < nvec) smooth8(f, inv_s, idx * 8);
+        m = __builtin_fmaxf(m, absmax8(f));
+    }
+    const float a = wave_max(m);
+    const float r = a > 0.0f ? 127.0f / a : 0.0f;
+    if (lane == 0) scale[row] = a / 127.0f;
+    v2u* out = (v2u*)(xq + row * (int64_t)c_i);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = lane + i * 64;
+        if (idx < nvec) {
+            float f[8];
+            unpack8<BF16>(raw[i], f);
+            if (inv_s) smooth8(f, inv_s, idx * 8);
+            out[idx] = quant8(f, r);
+        }
+    }
+}
+
+// Rows wider than the register-resident variants cover: two passes over the row (second one is
+// served by the caches for any realistic width).
+template <bool BF16>
+__global__ __launch_bounds__(256) void quant_per_token_stream(const uint16_t* __restrict__ x, int64_t ldx, int c_i,
+                                                             const float* __restrict__ inv_s, float* __restrict__ scale,
+                                                             int8_t* __restrict__ xq)
+{
+    __shared__ float red[4];
+    const int64_t row = blockIdx.x;
+    const v4u* xr = (const v4u*)(x + row * ldx);
+    const int nvec = c_i >> 3;
+    float m = 0.0f;
+    for (int idx = threadIdx.x; idx < nvec; idx += 256) {
+        float f[8];
+        unpack8<BF16>(xr[idx], f);
+        if (inv_s) smooth8(f, inv_s, idx * 8);
+        m = __builtin_fmaxf(m, absmax8(f));
+    }
+    const float a = block_max_256(m, red);
+    const float r = a > 0.0f ? 127.0f / a : 0.0f;
+    if (threadIdx.x == 0) scale[row] = a / 127.0f;
+    v2u* out = (v2u*)(xq + row * (int64_t)c_i);
+    for (int idx = threadIdx.x; idx < nvec; idx += 256) {
+        float f[8];
+        unpack8<BF16>(xr[idx], f);
+        if (inv_s) smooth8(f, inv_s, idx * 8);
+        out[idx] = quant8(f, r);
+    }
+}
+
+// ---- per-tensor
+
+__global__ void fill_u32_kernel(uint32_t* p, uint32_t v, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// absmax over the whole [t, c_i] tensor -> *amax_bits (bit pattern of a non-negative float; the
+// integer order of such patterns is the float order, so atomicMax on uint32 is exact).
+template <bool BF16>
+__global__ __launch_bounds__(256) void tensor_absmax_kernel(const uint16_t* __restrict__ x, int64_t ldx, int c_i, int64_t t,
+                                                           const float* __restrict__ inv_s, uint32_t* amax_bits)
+{
+    __shared__ float red[4];
+    const int nvec = c_i >> 3;
+    const int64_t total = t * (int64_t)nvec;
+    float m = 0.0f;
+    for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < total; g += (int64_t)gridDim.x * 256) {
+        const int64_t row = g / nvec;
+        const int idx = (int)(g - row * nvec);
+        float f[8];
+        unpack8<BF16>(((const v4u*)(x + row * ldx))[idx], f);
+        if (inv_s) smooth8(f, inv_s, idx * 8);
+        m = __builtin_fmaxf(m, absmax8(f));
+    }
+    m = block_max_256(m, red);
+    if (threadIdx.x == 0) atomicMax(amax_bits, __builtin_bit_cast(uint32_t, m));
+}
+
+// Elementwise quantization with one step for the whole tensor.  DYNAMIC: the step comes from the
+// absmax pass (and is written to scale[0]); otherwise scale[0] holds the calibrated Delta.
+template <bool BF16, bool DYNAMIC>
+__global__ __launch_bounds__(256) void quant_per_tensor_kernel(const uint16_t* __restrict__ x, int64_t ldx, int c_i, int64_t t,
+                                                              const float* __restrict__ inv_s, float* scale,
+                                                              const uint32_t* amax_bits, int8_t* __restrict__ xq)
+{
+    float r;
+    if (DYNAMIC) {
+        const float a = __builtin_bit_cast(float, *amax_bits);
+        r = a > 0.0f ? 127.0f / a : 0.0f;
+        if (blockIdx.x == 0 && threadIdx.x == 0) scale[0] = a / 127.0f;
+    } else {
+        const float delta = scale[0];
+        r = delta > 0.0f ? 1.0f / delta : 0.0f;
+    }
+    const int nvec = c_i >> 3;
+    const int64_t total = t * (int64_t)nvec;
+    for (int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x; g < total; g += (int64_t)gridDim.x * 256) {
+        const int64_t row = g / nvec;
+        const int idx = (int)(g - row * nvec);
+        float f[8];
+        unpack8<BF16>(__builtin_nontemporal_load((const v4u*)(x + row * ldx) + idx), f);
+        if (inv_s) smooth8(f, inv_s, idx * 8);
+        __builtin_nontemporal_store(quant8(f, r), (v2u*)(xq + row * (int64_t)c_i) + idx);
+    }
+}
+
+// Per-channel calibration statistic: out_j = max_t |x_tj| (bit patterns, see above).
+template <bool BF16>
+__global__ __launch_bounds__(256) void act_absmax_per_channel_kernel(const uint16_t* __restrict__ x, int c_i, int64_t t,
+                                                                    uint32_t* out_bits)
+{
+    const int nvec = c_i >> 3;
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= nvec) return;
+    float m[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int64_t row = blockIdx.y; row < t; row += gridDim.y) {
+        float f[8];
+        unpack8<BF16>(((const v4u*)(x + row * (int64_t)c_i))[idx], f);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) m[e] = __builtin_fmaxf(m[e], __builtin_fabsf(f[e]));
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) atomicMax(out_bits + idx * 8 + e, __builtin_bit_cast(uint32_t, m[e]));
+}
+
+template <bool BF16>
+void launch_per_token(const uint16_t* x, int64_t ldx, int c_i, int64_t t, const float* inv_s, float* scale, int8_t* xq,
+                      hipStream_t st)
+{
+    const int nvec = c_i >> 3;
+#define SQ_WAVE(NV) hipLaunchKernelGGL((quant_per_token_wave<BF16, NV>), dim3((unsigned)((t + 3) / 4)), dim3(256), 0, st, x, ldx, c_i, t, inv_s, scale, xq)
+#define SQ_BLOCK(NV) hipLaunchKernelGGL((quant_per_token_block<BF16, NV>), dim3((unsigned)t), dim3(256), 0, st, x, ldx, c_i, inv_s, scale, xq)
+    if (nvec <= 64) SQ_WAVE(1);
+    else if (nvec <= 128) SQ_WAVE(2);
+    else if (nvec <= 256) SQ_BLOCK(1);
+    else if (nvec <= 512) SQ_BLOCK(2);
+    else if (nvec <= 1024) SQ_BLOCK(4);
+    else if (nvec <= 1536) SQ_BLOCK(6);
+    else if (nvec <= 2048) SQ_BLOCK(8);
+    else if (nvec <= 3072) SQ_BLOCK(12);
+    else if (nvec <= 4096) SQ_BLOCK(16);
+    else if (nvec <= 6144) SQ_BLOCK(24);
+    else if (nvec <= 8192) SQ_BLOCK(32);
+    else hipLaunchKernelGGL((quant_per_token_stream<BF16>), dim3((unsigned)t), dim3(256), 0, st, x, ldx, c_i, inv_s, scale, xq);
+#undef SQ_WAVE
+#undef SQ_BLOCK
+}
+
+int grid_for(int64_t work_items)
+{
+    int64_t blocks = (work_items + 255) / 256;
+    const int64_t cap = 256 * 16;
+    return (int)(blocks < 1 ? 1 : (blocks > cap ? cap : blocks));
+}
+
+}  // namespace
+
+extern "C" {
+
+sq_status sq_quantize_act(const void* x, sq_dtype dtype, int64_t t, int64_t c_i, int64_t ldx, const float* inv_s,
+                          sq_act_mode mode, float* scale, int8_t* xq, void* workspace, size_t ws_bytes, void* stream)
+{
+    if (!x || !scale || !xq) return SQ_ERR_NULL;
+    if (t <= 0 || c_i <= 0 || ldx < c_i || t >= ((int64_t)1 << 31) || c_i >= ((int64_t)1 << 31)) return SQ_ERR_SHAPE;
+    if (dtype != SQ_F16 && dtype != SQ_BF16) return SQ_ERR_UNSUPPORTED;
+    if (mode != SQ_PER_TOKEN_DYNAMIC && mode != SQ_PER_TENSOR_DYNAMIC && mode != SQ_PER_TENSOR_STATIC)
+        return SQ_ERR_UNSUPPORTED;
+    if ((c_i & 15) || (ldx & 7) || !sq_aligned16(x) || !sq_aligned16(xq) || (inv_s && !sq_aligned16(inv_s)))
+        return SQ_ERR_ALIGN;
+    if (mode == SQ_PER_TENSOR_DYNAMIC && (!workspace || ws_bytes < sizeof(uint32_t))) return SQ_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const uint16_t* xp = (const uint16_t*)x;
+    const bool bf = dtype == SQ_BF16;
+    if (mode == SQ_PER_TOKEN_DYNAMIC) {
+        if (bf) launch_per_token<true>(xp, ldx, (int)c_i, t, inv_s, scale, xq, st);
+        else launch_per_token<false>(xp, ldx, (int)c_i, t, inv_s, scale, xq, st);
+        return sq_launch_status();
+    }
+    const int grid = grid_for(t * (c_i >> 3));
+    if (mode == SQ_PER_TENSOR_DYNAMIC) {
+        uint32_t* amax = (uint32_t*)workspace;
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, st, amax, 0u, 1);
+        if (bf) {
+            hipLaunchKernelGGL(tensor_absmax_kernel<true>, dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, amax);
+            hipLaunchKernelGGL((quant_per_tensor_kernel<true, true>), dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, amax, xq);
+        } else {
+            hipLaunchKernelGGL(tensor_absmax_kernel<false>, dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, amax);
+            hipLaunchKernelGGL((quant_per_tensor_kernel<false, true>), dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, amax, xq);
+        }
+    } else {
+        if (bf) hipLaunchKernelGGL((quant_per_tensor_kernel<true, false>), dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, (const uint32_t*)nullptr, xq);
+        else hipLaunchKernelGGL((quant_per_tensor_kernel<false, false>), dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, (const uint32_t*)nullptr, xq);
+    }
+    return sq_launch_status();
+}
+
+sq_status sq_act_absmax_per_channel(const void* x, sq_dtype dtype, int64_t t, int64_t c_i, float* out, void* stream)
+{
+    if (!x || !out) return SQ_ERR_NULL;
+    if (t <= 0 || c_i <= 0 || t >= ((int64_t)1 << 31) || c_i >= ((int64_t)1 << 31)) return SQ_ERR_SHAPE;
+    if (dtype != SQ_F16 && dtype != SQ_BF16) return SQ_ERR_UNSUPPORTED;
+    if ((c_i & 15) || !sq_aligned16(x) || !sq_aligned16(out)) return SQ_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((c_i + 255) / 256)), dim3(256), 0, st, (uint32_t*)out, 0u, (int)c_i);
+    const int nvec = (int)(c_i >> 3);
+    dim3 grid((unsigned)((nvec + 255) / 256), (unsigned)(t < 256 ? t : 256));
+    if (dtype == SQ_BF16)
+        hipLaunchKernelGGL(act_absmax_per_channel_kernel<true>, grid, dim3(256), 0, st, (const uint16_t*)x, (int)c_i, t, (uint32_t*)out);
+    else
+        hipLaunchKernelGGL(act_absmax_per_channel_kernel<false>, grid, dim3(256), 0, st, (const uint16_t*)x, (int)c_i, t, (uint32_t*)out);
+    return sq_launch_status();
+}
+
+}  // extern "C"

@@ -1,0 +1,207 @@
+// Row-wise 16-bit floating point operators that sit between the INT8 kernels (Sec. 4 keeps Softmax
+// and LayerNorm in FP16) fused with the quantization that feeds the next INT8 kernel, gfx950:
+//   * softmax over attention scores + quantization of P with the fixed step 1/127,
+//   * LayerNorm with the smoothing factors folded into gamma/beta + per-token dynamic quantization.
+// One row per 256-thread workgroup, the row held in registers: one HBM pass, 2 B in + 1 B out.
+#include "common.h"
+
+namespace {
+
+template <bool BF16> SQ_DEVICE void unpack8r(const v4u raw, float (&f)[8])
+{
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        f[2 * e] = load16_bits<BF16>(raw[e]);
+        f[2 * e + 1] = load16_bits<BF16>(raw[e] >> 16);
+    }
+}
+
+SQ_DEVICE float block_max_r(float v, float* red)
+{
+    v = wave_max(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return __builtin_fmaxf(__builtin_fmaxf(red[0], red[1]), __builtin_fmaxf(red[2], red[3]));
+}
+SQ_DEVICE float block_sum_r(float v, float* red)
+{
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+SQ_DEVICE v2u pack8(const int (&q)[8])
+{
+    v2u out;
+    out[0] = (q[0] & 0xff) | ((q[1] & 0xff) << 8) | ((q[2] & 0xff) << 16) | ((uint32_t)(q[3] & 0xff) << 24);
+    out[1] = (q[4] & 0xff) | ((q[5] & 0xff) << 8) | ((q[6] & 0xff) << 16) | ((uint32_t)(q[7] & 0xff) << 24);
+    return out;
+}
+
+template <bool BF16, int NV>
+__global__ __launch_bounds__(256) void softmax_quant_kernel(const uint16_t* __restrict__ s, int cols, int8_t* __restrict__ pq)
+{
+    __shared__ float red[4];
+    const int64_t row = blockIdx.x;
+    const v4u* sr = (const v4u*)(s + row * (int64_t)cols);
+    const int nvec = cols >> 3;
+    float z[NV][8];
+    float mx = -__builtin_inff();
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = threadIdx.x + i * 256;
+        if (idx < nvec) {
+            unpack8r<BF16>(__builtin_nontemporal_load(sr + idx), z[i]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) mx = __builtin_fmaxf(mx, z[i][e]);
+        }
+    }
+    mx = block_max_r(mx, red);
+    float sum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = threadIdx.x + i * 256;
+        if (idx < nvec) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                z[i][e] = expf(z[i][e] - mx);
+                sum += z[i][e];
+            }
+        }
+    }
+    sum = block_sum_r(sum, red);
+    const float inv = 1.0f / sum;
+    v2u* out = (v2u*)(pq + row * (int64_t)cols);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = threadIdx.x + i * 256;
+        if (idx < nvec) {
+            int q[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                // probability rounded to the 16-bit type first (the softmax output is a 16-bit tensor)
+                const float p16 = load16_bits<BF16>(store16_bits<BF16>(z[i][e] * inv));
+                q[e] = round_code(p16 * 127.0f);
+            }
+            __builtin_nontemporal_store(pack8(q), out + idx);
+        }
+    }
+}
+
+template <bool BF16, int NV>
+__global__ __launch_bounds__(256) void ln_quant_kernel(const uint16_t* __restrict__ x, int c_i, const float* __restrict__ gamma_f,
+                                                      const float* __restrict__ beta_f, float eps, float* __restrict__ scale,
+                                                      int8_t* __restrict__ xq)
+{
+    __shared__ float red[4];
+    const int64_t row = blockIdx.x;
+    const v4u* xr = (const v4u*)(x + row * (int64_t)c_i);
+    const int nvec = c_i >> 3;
+    float f[NV][8];
+    float sum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = threadIdx.x + i * 256;
+        if (idx < nvec) {
+            unpack8r<BF16>(__builtin_nontemporal_load(xr + idx), f[i]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sum += f[i][e];
+        }
+    }
+    const float mean = block_sum_r(sum, red) / (float)c_i;
+    float sq = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = threadIdx.x + i * 256;
+        if (idx < nvec) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float d = f[i][e] - mean;
+                sq += d * d;
+            }
+        }
+    }
+    const float var = block_sum_r(sq, red) / (float)c_i;
+    const float rstd = 1.0f / sqrtf(var + eps);
+    float m = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = threadIdx.x + i * 256;
+        if (idx < nvec) {
+            const float4 g0 = *(const float4*)(gamma_f + idx * 8), g1 = *(const float4*)(gamma_f + idx * 8 + 4);
+            const float4 b0 = *(const float4*)(beta_f + idx * 8), b1 = *(const float4*)(beta_f + idx * 8 + 4);
+            const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+            const float b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                f[i][e] = (f[i][e] - mean) * rstd * g[e] + b[e];
+                m = __builtin_fmaxf(m, __builtin_fabsf(f[i][e]));
+            }
+        }
+    }
+    const float a = block_max_r(m, red);
+    const float r = a > 0.0f ? 127.0f / a : 0.0f;
+    if (threadIdx.x == 0) scale[row] = a / 127.0f;
+    v2u* out = (v2u*)(xq + row * (int64_t)c_i);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = threadIdx.x + i * 256;
+        if (idx < nvec) {
+            int q[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) q[e] = round_code(f[i][e] * r);
+            __builtin_nontemporal_store(pack8(q), out + idx);
+        }
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+sq_status sq_softmax_quant_p(const void* s, sq_dtype dtype, int64_t rows, int64_t cols, int8_t* pq, void* stream)
+{
+    if (!s || !pq) return SQ_ERR_NULL;
+    if (rows <= 0 || cols <= 0 || rows >= ((int64_t)1 << 31)) return SQ_ERR_SHAPE;
+    if (dtype != SQ_F16 && dtype != SQ_BF16) return SQ_ERR_UNSUPPORTED;
+    if (cols > 8 * 256 * 8) return SQ_ERR_UNSUPPORTED;  // rows up to 16384 scores
+    if ((cols & 7) || !sq_aligned16(s) || !sq_aligned16(pq)) return SQ_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    const int nvec = (int)(cols >> 3);
+    const uint16_t* sp = (const uint16_t*)s;
+#define SQ_SM(BF, NV) hipLaunchKernelGGL((softmax_quant_kernel<BF, NV>), dim3((unsigned)rows), dim3(256), 0, st, sp, (int)cols, pq)
+    if (dtype == SQ_BF16) {
+        if (nvec <= 256) SQ_SM(true, 1); else if (nvec <= 512) SQ_SM(true, 2); else if (nvec <= 1024) SQ_SM(true, 4); else SQ_SM(true, 8);
+    } else {
+        if (nvec <= 256) SQ_SM(false, 1); else if (nvec <= 512) SQ_SM(false, 2); else if (nvec <= 1024) SQ_SM(false, 4); else SQ_SM(false, 8);
+    }
+#undef SQ_SM
+    return sq_launch_status();
+}
+
+sq_status sq_ln_quantize(const void* x, sq_dtype dtype, int64_t t, int64_t c_i, const float* gamma_f, const float* beta_f,
+                         float eps, float* scale, int8_t* xq, void* stream)
+{
+    if (!x || !gamma_f || !beta_f || !scale || !xq) return SQ_ERR_NULL;
+    if (t <= 0 || c_i <= 0 || t >= ((int64_t)1 << 31)) return SQ_ERR_SHAPE;
+    if (dtype != SQ_F16 && dtype != SQ_BF16) return SQ_ERR_UNSUPPORTED;
+    if (c_i > 8 * 256 * 8) return SQ_ERR_UNSUPPORTED;  // hidden sizes up to 16384
+    if ((c_i & 15) || !sq_aligned16(x) || !sq_aligned16(xq) || !sq_aligned16(gamma_f) || !sq_aligned16(beta_f))
+        return SQ_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    const int nvec = (int)(c_i >> 3);
+    const uint16_t* xp = (const uint16_t*)x;
+#define SQ_LN(BF, NV) hipLaunchKernelGGL((ln_quant_kernel<BF, NV>), dim3((unsigned)t), dim3(256), 0, st, xp, (int)c_i, gamma_f, beta_f, eps, scale, xq)
+    if (dtype == SQ_BF16) {
+        if (nvec <= 256) SQ_LN(true, 1); else if (nvec <= 512) SQ_LN(true, 2); else if (nvec <= 1024) SQ_LN(true, 4); else SQ_LN(true, 8);
+    } else {
+        if (nvec <= 256) SQ_LN(false, 1); else if (nvec <= 512) SQ_LN(false, 2); else if (nvec <= 1024) SQ_LN(false, 4); else SQ_LN(false, 8);
+    }
+#undef SQ_LN
+    return sq_launch_status();
+}
+
+}  // extern "C"

@@ -1,0 +1,133 @@
+// Offline weight preparation, gfx950: the statistics of Eq. 4, the smoothed weight of Eq. 3 and its
+// per-tensor quantization by Eq. 1, written transposed ([C_o, C_i], contraction index contiguous)
+// for the GEMM.  One-off work per layer: kept simple, coalesced on both sides of the transpose.
+#include "common.h"
+
+namespace {
+
+template <bool BF16> SQ_DEVICE void unpack8w(const v4u raw, float (&f)[8])
+{
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        f[2 * e] = load16_bits<BF16>(raw[e]);
+        f[2 * e + 1] = load16_bits<BF16>(raw[e] >> 16);
+    }
+}
+
+SQ_DEVICE float block_max_256w(float v, float* red)
+{
+    v = wave_max(v);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    const float r = __builtin_fmaxf(__builtin_fmaxf(red[0], red[1]), __builtin_fmaxf(red[2], red[3]));
+    __syncthreads();
+    return r;
+}
+
+// out_j = max_n |W_jn| * (s ? s_j : 1); one workgroup per input channel j (row of W).
+// If tensor_bits is given, also folds the row maxima into the tensor-wide maximum.
+template <bool BF16>
+__global__ __launch_bounds__(256) void weight_row_absmax_kernel(const uint16_t* __restrict__ w, int c_i, int c_o,
+                                                               const float* __restrict__ s, float* row_out,
+                                                               uint32_t* tensor_bits)
+{
+    __shared__ float red[4];
+    const int nvec = c_o >> 3;
+    for (int j = blockIdx.x; j < c_i; j += gridDim.x) {
+        const v4u* wr = (const v4u*)(w + (int64_t)j * c_o);
+        const float sj = s ? s[j] : 1.0f;
+        float m = 0.0f;
+        for (int idx = threadIdx.x; idx < nvec; idx += 256) {
+            float f[8];
+            unpack8w<BF16>(wr[idx], f);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) m = __builtin_fmaxf(m, __builtin_fabsf(s ? f[e] * sj : f[e]));
+        }
+        m = block_max_256w(m, red);
+        if (threadIdx.x == 0) {
+            if (row_out) row_out[j] = m;
+            if (tensor_bits) atomicMax(tensor_bits, __builtin_bit_cast(uint32_t, m));
+        }
+    }
+}
+
+__global__ void zero_u32_kernel(uint32_t* p) { if (threadIdx.x == 0) *p = 0u; }
+
+// 64 (input channels) x 64 (output channels) tile: read along C_o, quantize, transpose through LDS,
+// write along C_i.
+template <bool BF16>
+__global__ __launch_bounds__(256) void weight_quant_transpose_kernel(const uint16_t* __restrict__ w, int c_i, int c_o,
+                                                                    const float* __restrict__ s,
+                                                                    const uint32_t* amax_bits, float* w_scale,
+                                                                    int8_t* __restrict__ wq)
+{
+    __shared__ __attribute__((aligned(16))) int8_t tileT[64][80];  // [n][j], padded pitch
+    const float a = __builtin_bit_cast(float, *amax_bits);
+    const float r = a > 0.0f ? 127.0f / a : 0.0f;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) w_scale[0] = a / 127.0f;
+    const int j0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int v = threadIdx.x + h * 256;  // 512 vectors: 64 rows x 8 vectors of 8 channels
+        const int jl = v >> 3, nl = (v & 7) * 8;
+        const int j = j0 + jl, n = n0 + nl;
+        if (j < c_i && n < c_o) {  // c_o % 8 == 0: a vector is inside or outside as a whole
+            float f[8];
+            unpack8w<BF16>(*(const v4u*)(w + (int64_t)j * c_o + n), f);
+            const float sj = s ? s[j] : 1.0f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) tileT[nl + e][jl] = (int8_t)round_code((s ? f[e] * sj : f[e]) * r);
+        }
+    }
+    __syncthreads();
+    {
+        const int nl = threadIdx.x >> 2, jc = (threadIdx.x & 3) * 16;
+        const int n = n0 + nl, j = j0 + jc;
+        if (n < c_o && j < c_i)  // c_i % 16 == 0
+            *(v4u*)(wq + (int64_t)n * c_i + j) = *(const v4u*)&tileT[nl][jc];
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+sq_status sq_weight_absmax_per_in_channel(const void* w, sq_dtype dtype, int64_t c_i, int64_t c_o, float* out,
+                                          void* stream)
+{
+    if (!w || !out) return SQ_ERR_NULL;
+    if (c_i <= 0 || c_o <= 0 || c_i >= ((int64_t)1 << 31) || c_o >= ((int64_t)1 << 31)) return SQ_ERR_SHAPE;
+    if (dtype != SQ_F16 && dtype != SQ_BF16) return SQ_ERR_UNSUPPORTED;
+    if ((c_o & 7) || !sq_aligned16(w)) return SQ_ERR_ALIGN;
+    const unsigned grid = (unsigned)(c_i < 65535 ? c_i : 65535);
+    if (dtype == SQ_BF16)
+        hipLaunchKernelGGL(weight_row_absmax_kernel<true>, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const uint16_t*)w, (int)c_i, (int)c_o, (const float*)nullptr, out, (uint32_t*)nullptr);
+    else
+        hipLaunchKernelGGL(weight_row_absmax_kernel<false>, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const uint16_t*)w, (int)c_i, (int)c_o, (const float*)nullptr, out, (uint32_t*)nullptr);
+    return sq_launch_status();
+}
+
+sq_status sq_prepare_weight(const void* w, sq_dtype dtype, const float* s, int64_t c_i, int64_t c_o, int8_t* wq,
+                            float* w_scale, void* workspace, size_t ws_bytes, void* stream)
+{
+    if (!w || !wq || !w_scale) return SQ_ERR_NULL;
+    if (c_i <= 0 || c_o <= 0 || c_i >= ((int64_t)1 << 31) || c_o >= ((int64_t)1 << 31)) return SQ_ERR_SHAPE;
+    if (dtype != SQ_F16 && dtype != SQ_BF16) return SQ_ERR_UNSUPPORTED;
+    if ((c_i & 15) || (c_o & 7) || !sq_aligned16(w) || !sq_aligned16(wq)) return SQ_ERR_ALIGN;
+    if (!workspace || ws_bytes < sizeof(uint32_t)) return SQ_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    uint32_t* amax = (uint32_t*)workspace;
+    hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(64), 0, st, amax);
+    const unsigned grid1 = (unsigned)(c_i < 4096 ? c_i : 4096);
+    dim3 grid2((unsigned)((c_o + 63) / 64), (unsigned)((c_i + 63) / 64));
+    if (dtype == SQ_BF16) {
+        hipLaunchKernelGGL(weight_row_absmax_kernel<true>, dim3(grid1), dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, (float*)nullptr, amax);
+        hipLaunchKernelGGL(weight_quant_transpose_kernel<true>, grid2, dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, amax, w_scale, wq);
+    } else {
+        hipLaunchKernelGGL(weight_row_absmax_kernel<false>, dim3(grid1), dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, (float*)nullptr, amax);
+        hipLaunchKernelGGL(weight_quant_transpose_kernel<false>, grid2, dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, amax, w_scale, wq);
+    }
+    return sq_launch_status();
+}
+
+}  // extern "C"

