@@ -8,10 +8,10 @@
 // Design (CDNA4):
 //  * v_mfma_i32_32x32x32_i8, one wave owns a (MI*32) x (NI*32) block of accumulators.
 //  * Operand tiles travel HBM -> LDS with global_load_lds_dwordx4 (no VGPR staging), NSTAGE deep.
-//    LDS holds a tile as 16-row blocks; inside a block the 16-byte K-chunks are stored
-//    [chunk][row], so (a) one wave-wide load instruction fills 1 KB contiguous LDS from 16 rows x
-//    64 contiguous bytes of global memory and (b) every 16-lane group of an MFMA operand read
-//    (ds_read_b128) touches 256 contiguous bytes: no bank conflicts by construction.
+//    LDS holds a tile as 16-row blocks of 1 KB, row-major (64 B per row) with the four 16-byte
+//    K-chunks of a row XOR-permuted: (a) one wave-wide load instruction fills a block from 16 rows
+//    x 64 contiguous bytes of global memory, four neighbouring lanes per row (coalesced), and (b)
+//    the ds_read_b128 operand reads of the MFMAs spread over all banks.
 //  * One s_barrier per 64-wide K step; operand fragments are double buffered in registers so the
 //    LDS reads of the next half step are in flight while the MFMAs of this half step issue.
 //  * Tiles are enumerated XCD-aware: the workgroups an XCD runs concurrently cover a compact
@@ -83,7 +83,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
     static_assert(NSTAGE >= 3 && (NSTAGE - 2) * LPS <= 63, "pipeline depth exceeds the 6-bit vmcnt");
     static_assert(NSTAGE * STAGE <= 160 * 1024, "LDS budget");
-    __shared__ __attribute__((aligned(1024))) char smem[NSTAGE * STAGE];
+    constexpr int EPI_BYTES = EPI == EPI_DEQUANT ? BM * (BN * 2 + 16) : 0;
+    constexpr int SMEM_BYTES = NSTAGE * STAGE > EPI_BYTES ? NSTAGE * STAGE : EPI_BYTES;
+    static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
+    __shared__ __attribute__((aligned(1024))) char smem[SMEM_BYTES];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -122,27 +125,37 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
     const int8_t* Ab = p.A + (int64_t)batch * p.strideA + (int64_t)m0 * p.lda + (int64_t)kbeg * BK;
     const int8_t* Bb = p.B + (int64_t)batch * p.strideB + (int64_t)n0 * p.ldb + (int64_t)kbeg * BK;
 
-    // ---- global -> LDS load slots of this wave.  Slot i moves 16-row block (i*NW + wave); lane l
-    // fetches row (l & 15), chunk (l >> 4) and lands at LDS byte l*16 of the block's 1 KB.
-    const int chunk = lane >> 4;
+    // ---- global -> LDS load slots of this wave.  Slot i moves 16-row block (i*NW + wave), 1 KB per
+    // stage.  Lane l lands at LDS byte l*16 of the block, i.e. the block is row-major (64 B per row),
+    // and fetches row (l >> 2): four neighbouring lanes read one contiguous 64-byte segment, which
+    // the vector memory path coalesces.  Inside a row the four 16-byte chunks are permuted
+    // (position = chunk ^ swz(row)) so that the MFMA operand reads below stay bank-conflict free.
+    auto swz = [](int r) { return ((r >> 1) & 3) ^ ((r >> 3) & 1); };
+    const int chunk = (lane & 3) ^ swz(lane >> 2);
     uint32_t offA[SA], offB[SB];
     int ldsA[SA], ldsB[SB];
 #pragma unroll
     for (int i = 0; i < SA; ++i) {
         const int rb = (i * NW + wave) % RBA;  // wraps only when RBA is not a multiple of NW: a benign duplicate
-        int row = rb * 16 + (lane & 15);
+        int row = rb * 16 + (lane >> 2);
         const int last = p.M - 1 - m0;
         row = row < last ? row : last;
         offA[i] = (uint32_t)(row * (int)p.lda + chunk * 16);
+#ifdef SQ_EXPERIMENT_BLOCKED
+        offA[i] = (uint32_t)(rb * 16 * (int)p.lda + lane * 16);
+#endif
         ldsA[i] = rb * 1024;
     }
 #pragma unroll
     for (int i = 0; i < SB; ++i) {
         const int rb = (i * NW + wave) % RBB;
-        int row = rb * 16 + (lane & 15);
+        int row = rb * 16 + (lane >> 2);
         const int last = p.N - 1 - n0;
         row = row < last ? row : last;
         offB[i] = (uint32_t)(row * (int)p.ldb + chunk * 16);
+#ifdef SQ_EXPERIMENT_BLOCKED
+        offB[i] = (uint32_t)(rb * 16 * (int)p.ldb + lane * 16);
+#endif
         ldsB[i] = A_BYTES + rb * 1024;
     }
 
@@ -150,8 +163,13 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
     // re-read chunk 0 (valid memory); their A fragments are zeroed in registers before the MFMAs.
     const bool has_tail = tail_chunks != 0 && (kbeg + nk == nk_total);
     auto issue_stage = [&](int kt, int buf) {
+#ifdef SQ_EXPERIMENT_BLOCKED
+        const int8_t* a = Ab + (int64_t)kt * 1024;
+        const int8_t* b = Bb + (int64_t)kt * 1024;
+#else
         const int8_t* a = Ab + (int64_t)kt * BK;
         const int8_t* b = Bb + (int64_t)kt * BK;
+#endif
         char* base = smem + buf * STAGE;
         const uint32_t back = (has_tail && kt == nk - 1 && chunk >= tail_chunks) ? (uint32_t)chunk * 16u : 0u;
 #pragma unroll
@@ -163,8 +181,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
     };
 
     // ---- MFMA operand fragments.  For the 32x32x32 MFMA lane l feeds row (l & 31) with the 16
-    // bytes of K-chunk (l >> 5) of the 32-wide K step.
-    const int lane_off = ((lane & 31) >> 4) * 1024 + (lane >> 5) * 256 + (lane & 15) * 16;
+    // bytes of K-chunk kk*2 + (l >> 5) of the 64-wide K step; chunk c of row r sits at position
+    // c ^ swz(r), and kk only flips bit 1 of the position: byte address ^ 32.
+    const int frow = lane & 15;
+    const int lane_off = ((lane & 31) >> 4) * 1024 + frow * 64 + (((lane >> 5) ^ swz(frow)) * 16);
     const int fragA0 = wm * (WM / 16) * 1024 + lane_off;
     const int fragB0 = A_BYTES + wn * (WN / 16) * 1024 + lane_off;
 
@@ -178,8 +198,11 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
     auto read_frags = [&](v4i(&fa)[MI], v4i(&fb)[NI], int buf, int kk) {
-        const char* sa = smem + buf * STAGE + fragA0 + kk * 512;
-        const char* sb = smem + buf * STAGE + fragB0 + kk * 512;
+#ifdef SQ_ABL_NOLDS
+        if (p.K != 1) return;
+#endif
+        const char* sa = smem + buf * STAGE + (fragA0 ^ (kk * 32));
+        const char* sb = smem + buf * STAGE + (fragB0 ^ (kk * 32));
 #pragma unroll
         for (int i = 0; i < MI; ++i) fa[i] = *(const v4i*)(sa + i * 2048);
 #pragma unroll
@@ -190,7 +213,11 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
         for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int j = 0; j < NI; ++j)
+#ifdef SQ_ABL_NOMFMA
+                acc[i][j][0] += fa[i][0] + fb[j][0];
+#else
                 acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+#endif
     };
     // Scheduling hint for one half step (MI+NI fragment reads of the next half, MI*NI MFMAs of this
     // one): interleave the LDS reads with the MFMAs so the four waves of the workgroup do not hit
@@ -230,9 +257,15 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
         const int nbuf = buf + 1 == NSTAGE ? 0 : buf + 1;
         int last = it + NSTAGE - 2;
         last = last < nk - 1 ? last : nk - 1;
+#ifndef SQ_ABL_NOLOAD
         wait_stages<LPS, NSTAGE - 3>(last - (it + 1));
+#endif
+#ifndef SQ_ABL_NOBAR
         __builtin_amdgcn_s_barrier();
+#endif
+#ifndef SQ_ABL_NOLOAD
         if (it + NSTAGE - 1 < nk) issue_stage(it + NSTAGE - 1, buf == 0 ? NSTAGE - 1 : buf - 1);
+#endif
         read_frags(fa0, fb0, nbuf, 0);
         mfma_all(fa1, fb1);
         interleave_hint();
@@ -271,8 +304,37 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
                 }
             }
     } else {
+        // The 16-bit tile is staged in LDS (free once the K loop is over) so that global memory is
+        // written in whole 512-byte row segments, 16 bytes per lane, instead of 2-byte scatters; the
+        // residual tile is fetched the same way.  Row pitch +16 B keeps the two half-waves (4 rows
+        // apart) on different banks.
+        constexpr int PITCH = BN * 2 + 16;
+        constexpr int CPR = BN / 8;  // 16-byte chunks per tile row
+        static_assert(BM * PITCH <= SMEM_BYTES, "epilogue staging must fit in the LDS allocation");
         uint16_t* C = (uint16_t*)p.C + (int64_t)batch * p.strideC;
         const uint16_t* R = (const uint16_t*)p.residual;
+        const bool vec_ok = (p.N & 7) == 0;  // 16-byte chunks never straddle the row end and stay aligned
+        __builtin_amdgcn_s_barrier();        // every wave has finished reading operand tiles from LDS
+        if (R) {
+            for (int q = threadIdx.x; q < BM * CPR; q += NW * 64) {
+                const int r = q / CPR, c8 = (q - r * CPR) * 8;
+                const int row = m0 + r, col = n0 + c8;
+                v4u val = {0, 0, 0, 0};
+                if (row < p.M && col < p.N) {
+                    const uint16_t* src = R + (int64_t)row * p.N + col;
+                    if (vec_ok) {
+                        val = *(const v4u*)src;
+                    } else {
+                        uint32_t e[8];
+#pragma unroll
+                        for (int t = 0; t < 8; ++t) e[t] = (col + t < p.N) ? src[t] : 0u;
+                        val = v4u{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+                    }
+                }
+                *(v4u*)(smem + r * PITCH + c8 * 2) = val;
+            }
+            __syncthreads();
+        }
         const float ws = p.x_scale ? p.w_scale[0] : 0.0f;
         const float xs0 = (p.x_scale && !p.per_token) ? p.x_scale[0] : 0.0f;
         float bj[NI];
@@ -285,23 +347,35 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
         for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const int row = m0 + wm * WM + i * 32 + 8 * (v >> 2) + row_l + (v & 3);
-                if (row < p.M) {
-                    float c;
-                    if (p.x_scale) c = (p.per_token ? p.x_scale[row] : xs0) * ws;
-                    else c = p.alpha;
+                const int lrow = wm * WM + i * 32 + 8 * (v >> 2) + row_l + (v & 3);
+                const int row = m0 + lrow;
+                float c;
+                if (p.x_scale) c = (p.per_token ? p.x_scale[row < p.M ? row : p.M - 1] : xs0) * ws;
+                else c = p.alpha;
 #pragma unroll
-                    for (int j = 0; j < NI; ++j) {
-                        const int col = n0 + wn * WN + j * 32 + col_l;
-                        if (col < p.N) {
-                            const int64_t idx = (int64_t)row * p.N + col;
-                            const uint32_t rb = R ? R[idx] : 0u;
-                            C[idx] = (uint16_t)dequant_one<BF16>(acc[i][j][v], c, bj[j], p.bias != nullptr, p.relu != 0,
-                                                                 rb, R != nullptr);
-                        }
-                    }
+                for (int j = 0; j < NI; ++j) {
+                    uint16_t* slot = (uint16_t*)(smem + lrow * PITCH + (wn * WN + j * 32 + col_l) * 2);
+                    const uint32_t rb = R ? (uint32_t)*slot : 0u;
+                    *slot = (uint16_t)dequant_one<BF16>(acc[i][j][v], c, bj[j], p.bias != nullptr, p.relu != 0, rb,
+                                                        R != nullptr);
                 }
             }
+        __syncthreads();
+        for (int q = threadIdx.x; q < BM * CPR; q += NW * 64) {
+            const int r = q / CPR, c8 = (q - r * CPR) * 8;
+            const int row = m0 + r, col = n0 + c8;
+            if (row < p.M && col < p.N) {
+                const v4u val = *(const v4u*)(smem + r * PITCH + c8 * 2);
+                uint16_t* dst = C + (int64_t)row * p.N + col;
+                if (vec_ok) {
+                    __builtin_nontemporal_store(val, (v4u*)dst);
+                } else {
+#pragma unroll
+                    for (int t = 0; t < 8; ++t)
+                        if (col + t < p.N) dst[t] = (uint16_t)(val[t >> 1] >> ((t & 1) * 16));
+                }
+            }
+        }
     }
 }
 
