@@ -18,6 +18,8 @@
 //    block of output tiles, so its L2 serves the shared A rows / B rows.
 //  * Optional split-K writes int32 partial tiles to a workspace, reduced (exactly, int32) by a
 //    second small kernel that also runs the epilogue.
+#include <type_traits>
+
 #include "common.h"
 
 #define GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
@@ -343,23 +345,39 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
             const int col = n0 + wn * WN + j * 32 + col_l;
             bj[j] = (p.bias && col < p.N) ? p.bias[col] : 0.0f;
         }
+        // The optional terms are compile-time flags inside the 256-element loop (one uniform switch
+        // outside) so the common cases cost convert + multiply + round + LDS write per element.
+        auto phase1 = [&](auto HB, auto RL, auto HR) {
+            constexpr bool has_bias = decltype(HB)::value, relu = decltype(RL)::value, has_res = decltype(HR)::value;
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+            for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int lrow = wm * WM + i * 32 + 8 * (v >> 2) + row_l + (v & 3);
-                const int row = m0 + lrow;
-                float c;
-                if (p.x_scale) c = (p.per_token ? p.x_scale[row < p.M ? row : p.M - 1] : xs0) * ws;
-                else c = p.alpha;
+                for (int v = 0; v < 16; ++v) {
+                    const int lrow = wm * WM + i * 32 + 8 * (v >> 2) + row_l + (v & 3);
+                    const int row = m0 + lrow;
+                    float c;
+                    if (p.x_scale) c = (p.per_token ? p.x_scale[row < p.M ? row : p.M - 1] : xs0) * ws;
+                    else c = p.alpha;
 #pragma unroll
-                for (int j = 0; j < NI; ++j) {
-                    uint16_t* slot = (uint16_t*)(smem + lrow * PITCH + (wn * WN + j * 32 + col_l) * 2);
-                    const uint32_t rb = R ? (uint32_t)*slot : 0u;
-                    *slot = (uint16_t)dequant_one<BF16>(acc[i][j][v], c, bj[j], p.bias != nullptr, p.relu != 0, rb,
-                                                        R != nullptr);
+                    for (int j = 0; j < NI; ++j) {
+                        uint16_t* slot = (uint16_t*)(smem + lrow * PITCH + (wn * WN + j * 32 + col_l) * 2);
+                        const uint32_t rb = has_res ? (uint32_t)*slot : 0u;
+                        *slot = (uint16_t)dequant_one<BF16>(acc[i][j][v], c, bj[j], has_bias, relu, rb, has_res);
+                    }
                 }
-            }
+        };
+        using T_ = std::true_type;
+        using F_ = std::false_type;
+        switch ((p.bias ? 1 : 0) | (p.relu ? 2 : 0) | (R ? 4 : 0)) {
+            case 0: phase1(F_{}, F_{}, F_{}); break;
+            case 1: phase1(T_{}, F_{}, F_{}); break;
+            case 2: phase1(F_{}, T_{}, F_{}); break;
+            case 3: phase1(T_{}, T_{}, F_{}); break;
+            case 4: phase1(F_{}, F_{}, T_{}); break;
+            case 5: phase1(T_{}, F_{}, T_{}); break;
+            case 6: phase1(F_{}, T_{}, T_{}); break;
+            default: phase1(T_{}, T_{}, T_{}); break;
+        }
         __syncthreads();
         for (int q = threadIdx.x; q < BM * CPR; q += NW * 64) {
             const int r = q / CPR, c8 = (q - r * CPR) * 8;
