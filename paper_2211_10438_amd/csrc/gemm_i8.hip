@@ -74,14 +74,20 @@ SQ_DEVICE uint32_t dequant_one(int acc, float c, float bias, bool has_bias, bool
 }
 
 // BM x BN output tile per workgroup, WGM x WGN waves, BK = 64 bytes of K per pipeline stage.
-template <int BM, int BN, int WGM, int WGN, int NSTAGE, int EPI, bool BF16>
+// BT = false: B is [N, K] (K-contiguous rows, like A).  BT = true: B is [K, N] (the V operand of
+// attention's P V product): its tiles are read through registers, transposed bytewise in registers
+// and written to the same LDS layout, so the MFMA loop is identical.
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, int EPI, bool BF16, bool BT>
 __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArgs p)
 {
     constexpr int NW = WGM * WGN, BK = 64;
     constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
     constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE = A_BYTES + B_BYTES;
     constexpr int RBA = BM / 16, RBB = BN / 16;  // 16-row blocks per operand tile
-    constexpr int SA = (RBA + NW - 1) / NW, SB = (RBB + NW - 1) / NW, LPS = SA + SB;
+    constexpr int SA = (RBA + NW - 1) / NW, SB = BT ? 0 : (RBB + NW - 1) / NW;
+    constexpr int KR = BT ? BN / 16 : 0;  // BT: each lane moves a KR (k) x 4 (n) byte block per stage
+    constexpr int LPS = SA + SB + KR;     // vector-memory loads per wave per stage
+    static_assert(!BT || (NW == 4 && (BN == 256 || BN == 128)), "transposed-B path assumes 256 lanes");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
     static_assert(NSTAGE >= 3 && (NSTAGE - 2) * LPS <= 63, "pipeline depth exceeds the 6-bit vmcnt");
     static_assert(NSTAGE * STAGE <= 160 * 1024, "LDS budget");
@@ -125,7 +131,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
     const int tail_chunks = (p.K & (BK - 1)) >> 4;  // valid 16-byte chunks of the last K step (0 = all 4)
 
     const int8_t* Ab = p.A + (int64_t)batch * p.strideA + (int64_t)m0 * p.lda + (int64_t)kbeg * BK;
-    const int8_t* Bb = p.B + (int64_t)batch * p.strideB + (int64_t)n0 * p.ldb + (int64_t)kbeg * BK;
+    const int8_t* Bb = BT ? p.B + (int64_t)batch * p.strideB + n0
+                          : p.B + (int64_t)batch * p.strideB + (int64_t)n0 * p.ldb + (int64_t)kbeg * BK;
 
     // ---- global -> LDS load slots of this wave.  Slot i moves 16-row block (i*NW + wave), 1 KB per
     // stage.  Lane l lands at LDS byte l*16 of the block, i.e. the block is row-major (64 B per row),
@@ -134,8 +141,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
     // (position = chunk ^ swz(row)) so that the MFMA operand reads below stay bank-conflict free.
     auto swz = [](int r) { return ((r >> 1) & 3) ^ ((r >> 3) & 1); };
     const int chunk = (lane & 3) ^ swz(lane >> 2);
-    uint32_t offA[SA], offB[SB];
-    int ldsA[SA], ldsB[SB];
+    uint32_t offA[SA], offB[SB + 1];
+    int ldsA[SA], ldsB[SB + 1];
 #pragma unroll
     for (int i = 0; i < SA; ++i) {
         const int rb = (i * NW + wave) % RBA;  // wraps only when RBA is not a multiple of NW: a benign duplicate
@@ -143,9 +150,6 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
         const int last = p.M - 1 - m0;
         row = row < last ? row : last;
         offA[i] = (uint32_t)(row * (int)p.lda + chunk * 16);
-#ifdef SQ_EXPERIMENT_BLOCKED
-        offA[i] = (uint32_t)(rb * 16 * (int)p.lda + lane * 16);
-#endif
         ldsA[i] = rb * 1024;
     }
 #pragma unroll
@@ -155,9 +159,6 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
         const int last = p.N - 1 - n0;
         row = row < last ? row : last;
         offB[i] = (uint32_t)(row * (int)p.ldb + chunk * 16);
-#ifdef SQ_EXPERIMENT_BLOCKED
-        offB[i] = (uint32_t)(rb * 16 * (int)p.ldb + lane * 16);
-#endif
         ldsB[i] = A_BYTES + rb * 1024;
     }
 
@@ -165,13 +166,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
     // re-read chunk 0 (valid memory); their A fragments are zeroed in registers before the MFMAs.
     const bool has_tail = tail_chunks != 0 && (kbeg + nk == nk_total);
     auto issue_stage = [&](int kt, int buf) {
-#ifdef SQ_EXPERIMENT_BLOCKED
-        const int8_t* a = Ab + (int64_t)kt * 1024;
-        const int8_t* b = Bb + (int64_t)kt * 1024;
-#else
         const int8_t* a = Ab + (int64_t)kt * BK;
         const int8_t* b = Bb + (int64_t)kt * BK;
-#endif
         char* base = smem + buf * STAGE;
         const uint32_t back = (has_tail && kt == nk - 1 && chunk >= tail_chunks) ? (uint32_t)chunk * 16u : 0u;
 #pragma unroll
@@ -180,6 +176,52 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
 #pragma unroll
         for (int i = 0; i < SB; ++i)
             __builtin_amdgcn_global_load_lds(GPTR(b + (offB[i] - back)), LPTR(base + ldsB[i]), 16, 0, 0);
+    };
+
+    // ---- transposed-B path: lane block = KR consecutive k rows x 4 consecutive n columns.
+    uint32_t breg[KR + 1];
+    const int bt_cg = BT ? (int)(threadIdx.x % (BN / 4)) : 0;   // column group: columns 4*cg .. 4*cg+3
+    const int bt_ks = BT ? (int)(threadIdx.x / (BN / 4)) : 0;   // k slab: rows ks*KR .. ks*KR+KR-1 of the stage
+    int bt_col = bt_cg * 4;
+    if (BT && n0 + bt_col + 4 > p.N) bt_col = p.N - 4 - n0;      // ragged N tile: re-read valid columns
+    auto load_b = [&](int kt) {
+        if constexpr (BT) {
+            const int k0 = (kbeg + kt) * BK + bt_ks * KR;
+#pragma unroll
+            for (int j = 0; j < KR; ++j) {
+                int k = k0 + j;
+                k = k < p.K ? k : p.K - 1;  // K tail: any valid row (the A fragments there are zero)
+                breg[j] = *(const uint32_t*)(Bb + (int64_t)k * p.ldb + bt_col);
+            }
+        }
+    };
+    auto store_b = [&](int buf) {
+        if constexpr (BT) {
+            // 4x4 byte transposes: out[e][m] = bytes e of rows 4m .. 4m+3
+            uint32_t out[4][KR / 4 + 1];
+#pragma unroll
+            for (int m = 0; m < KR / 4; ++m) {
+                const uint32_t r0 = breg[4 * m], r1 = breg[4 * m + 1], r2 = breg[4 * m + 2], r3 = breg[4 * m + 3];
+                const uint32_t t0 = __builtin_amdgcn_perm(r1, r0, 0x05010400u), t1 = __builtin_amdgcn_perm(r1, r0, 0x07030602u);
+                const uint32_t u0 = __builtin_amdgcn_perm(r3, r2, 0x05010400u), u1 = __builtin_amdgcn_perm(r3, r2, 0x07030602u);
+                out[0][m] = __builtin_amdgcn_perm(u0, t0, 0x05040100u);
+                out[1][m] = __builtin_amdgcn_perm(u0, t0, 0x07060302u);
+                out[2][m] = __builtin_amdgcn_perm(u1, t1, 0x05040100u);
+                out[3][m] = __builtin_amdgcn_perm(u1, t1, 0x07060302u);
+            }
+            char* base = smem + buf * STAGE + A_BYTES;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int n = bt_cg * 4 + e, r = n & 15;
+                if constexpr (KR == 16) {
+                    const int pos = bt_ks ^ swz(r);
+                    *(v4u*)(base + (n >> 4) * 1024 + r * 64 + pos * 16) = v4u{out[e][0], out[e][1], out[e][2], out[e][3]};
+                } else {
+                    const int pos = (bt_ks >> 1) ^ swz(r);
+                    *(v2u*)(base + (n >> 4) * 1024 + r * 64 + pos * 16 + (bt_ks & 1) * 8) = v2u{out[e][0], out[e][1]};
+                }
+            }
+        }
     };
 
     // ---- MFMA operand fragments.  For the 32x32x32 MFMA lane l feeds row (l & 31) with the 16
@@ -200,9 +242,6 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
     auto read_frags = [&](v4i(&fa)[MI], v4i(&fb)[NI], int buf, int kk) {
-#ifdef SQ_ABL_NOLDS
-        if (p.K != 1) return;
-#endif
         const char* sa = smem + buf * STAGE + (fragA0 ^ (kk * 32));
         const char* sb = smem + buf * STAGE + (fragB0 ^ (kk * 32));
 #pragma unroll
@@ -215,11 +254,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
         for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int j = 0; j < NI; ++j)
-#ifdef SQ_ABL_NOMFMA
-                acc[i][j][0] += fa[i][0] + fb[j][0];
-#else
                 acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
-#endif
     };
     // Scheduling hint for one half step (MI+NI fragment reads of the next half, MI*NI MFMAs of this
     // one): interleave the LDS reads with the MFMAs so the four waves of the workgroup do not hit
@@ -240,7 +275,16 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
 #pragma unroll
     for (int s = 0; s < NSTAGE - 1; ++s)
         if (s < nk) issue_stage(s, s);
-    {
+    if constexpr (BT) {
+        // B stages 0 and 1 go through registers synchronously (which also drains the DMA loads above);
+        // stage 2 stays in registers and is written to LDS during K step 0.
+        load_b(0);
+        store_b(0);
+        if (1 < nk) { load_b(1); store_b(1); }
+        if (2 < nk) load_b(2);
+        wait_vmcnt_imm<KR>();
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    } else {
         const int inflight = nk < NSTAGE - 1 ? nk : NSTAGE - 1;
         wait_stages<LPS, NSTAGE - 2>(inflight - 1);
     }
@@ -259,15 +303,13 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
         const int nbuf = buf + 1 == NSTAGE ? 0 : buf + 1;
         int last = it + NSTAGE - 2;
         last = last < nk - 1 ? last : nk - 1;
-#ifndef SQ_ABL_NOLOAD
         wait_stages<LPS, NSTAGE - 3>(last - (it + 1));
-#endif
-#ifndef SQ_ABL_NOBAR
         __builtin_amdgcn_s_barrier();
-#endif
-#ifndef SQ_ABL_NOLOAD
+        if constexpr (BT) {
+            if (it + 2 < nk) store_b(buf + 2 >= NSTAGE ? buf + 2 - NSTAGE : buf + 2);
+            if (it + 3 < nk) load_b(it + 3);
+        }
         if (it + NSTAGE - 1 < nk) issue_stage(it + NSTAGE - 1, buf == 0 ? NSTAGE - 1 : buf - 1);
-#endif
         read_frags(fa0, fb0, nbuf, 0);
         mfma_all(fa1, fb1);
         interleave_hint();
@@ -422,7 +464,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs p, in
 // ---------------------------------------------------------------- host side: tile / split choice
 
 struct Plan {
-    int cfg;     // 0: 256x256 (prefill)  1: 128x256  2: 64x256  3: 32x256
+    int cfg;     // 0: 256x256 (prefill)  1: 128x256  2: 64x256  3: 32x256  4: 256x256 B^T  5: 256x128 B^T
     int bm, bn;
     int splits, iters_per_split;
     int tiles_m, tiles_n;
@@ -430,14 +472,20 @@ struct Plan {
 
 constexpr int kNumCU = 256;
 
-Plan make_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split)
+Plan make_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split, bool b_transposed = false)
 {
     Plan pl{};
-    if (M > 128) { pl.cfg = 0; pl.bm = 256; }
+    pl.bn = 256;
+    if (b_transposed) {
+        pl.bm = 256;
+        if (N <= 128) { pl.cfg = 5; pl.bn = 128; }
+        else pl.cfg = 4;
+        allow_split = false;
+    }
+    else if (M > 128) { pl.cfg = 0; pl.bm = 256; }
     else if (M > 64) { pl.cfg = 1; pl.bm = 128; }
     else if (M > 32) { pl.cfg = 2; pl.bm = 64; }
     else { pl.cfg = 3; pl.bm = 32; }
-    pl.bn = 256;
     pl.tiles_m = (int)((M + pl.bm - 1) / pl.bm);
     pl.tiles_n = (int)((N + pl.bn - 1) / pl.bn);
     const int nk = (int)((K + 63) / 64);
@@ -466,16 +514,23 @@ void launch_cfg(const Plan& pl, const GemmArgs& a, int batch, hipStream_t st)
 {
     dim3 grid((unsigned)(pl.tiles_m * pl.tiles_n * pl.splits), (unsigned)batch);
     switch (pl.cfg) {
-        case 0: hipLaunchKernelGGL((gemm_i8_kernel<256, 256, 2, 2, 4, EPI, BF16>), grid, dim3(256), 0, st, a); break;
-        case 1: hipLaunchKernelGGL((gemm_i8_kernel<128, 256, 1, 4, 6, EPI, BF16>), grid, dim3(256), 0, st, a); break;
-        case 2: hipLaunchKernelGGL((gemm_i8_kernel<64, 256, 1, 4, 7, EPI, BF16>), grid, dim3(256), 0, st, a); break;
-        default: hipLaunchKernelGGL((gemm_i8_kernel<32, 256, 1, 4, 8, EPI, BF16>), grid, dim3(256), 0, st, a); break;
+        case 0: hipLaunchKernelGGL((gemm_i8_kernel<256, 256, 2, 2, 4, EPI, BF16, false>), grid, dim3(256), 0, st, a); break;
+        case 1: hipLaunchKernelGGL((gemm_i8_kernel<128, 256, 1, 4, 6, EPI, BF16, false>), grid, dim3(256), 0, st, a); break;
+        case 2: hipLaunchKernelGGL((gemm_i8_kernel<64, 256, 1, 4, 7, EPI, BF16, false>), grid, dim3(256), 0, st, a); break;
+        case 3: hipLaunchKernelGGL((gemm_i8_kernel<32, 256, 1, 4, 8, EPI, BF16, false>), grid, dim3(256), 0, st, a); break;
+        default:
+            if constexpr (EPI == EPI_DEQUANT) {
+                if (pl.cfg == 4) hipLaunchKernelGGL((gemm_i8_kernel<256, 256, 2, 2, 4, EPI, BF16, true>), grid, dim3(256), 0, st, a);
+                else hipLaunchKernelGGL((gemm_i8_kernel<256, 128, 4, 1, 5, EPI, BF16, true>), grid, dim3(256), 0, st, a);
+            }
+            break;
     }
 }
 
-sq_status run_gemm(GemmArgs a, int64_t batch, bool to_i32, bool bf16, void* workspace, size_t ws_bytes, hipStream_t st)
+sq_status run_gemm(GemmArgs a, int64_t batch, bool to_i32, bool bf16, void* workspace, size_t ws_bytes, hipStream_t st,
+                   bool b_transposed = false)
 {
-    Plan pl = make_plan(a.M, a.N, a.K, batch, true);
+    Plan pl = make_plan(a.M, a.N, a.K, batch, true, b_transposed);
     a.tiles_m = pl.tiles_m;
     a.tiles_n = pl.tiles_n;
     a.splits = pl.splits;
@@ -562,14 +617,14 @@ sq_status sq_internal_bmm(const int8_t* a_, const int8_t* b_, int trans_b, float
                           int64_t batch, int64_t m, int64_t n, int64_t k, int64_t stride_a, int64_t stride_b,
                           int64_t stride_c, void* stream)
 {
-    if (!trans_b) return SQ_ERR_UNSUPPORTED;
     GemmArgs a{};
     a.A = a_; a.B = b_;
     a.M = (int)m; a.N = (int)n; a.K = (int)k;
-    a.lda = k; a.ldb = k;
+    a.lda = k;
+    a.ldb = trans_b ? k : n;  // trans_b: rows of B are K-contiguous; otherwise B is [k, n]
     a.strideA = stride_a; a.strideB = stride_b; a.strideC = stride_c;
     a.C = c; a.alpha = alpha;
-    return run_gemm(a, batch, false, out == SQ_BF16, nullptr, 0, (hipStream_t)stream);
+    return run_gemm(a, batch, false, out == SQ_BF16, nullptr, 0, (hipStream_t)stream, !trans_b);
 }
 
 }  // extern "C"
