@@ -51,18 +51,6 @@ struct GemmArgs {
 
 template <int N> SQ_DEVICE void wait_vmcnt_imm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-// Wait until at most min(m, MAXM) pipeline stages (LPS loads each, issued by this wave) are still
-// in flight.  s_waitcnt takes an immediate, hence the compile-time ladder.
-template <int LPS, int MAXM> SQ_DEVICE void wait_stages(int m)
-{
-    if constexpr (MAXM <= 0) {
-        wait_vmcnt_imm<0>();
-    } else {
-        if (m >= MAXM) wait_vmcnt_imm<MAXM * LPS>();
-        else wait_stages<LPS, MAXM - 1>(m);
-    }
-}
-
 template <bool BF16>
 SQ_DEVICE uint32_t dequant_one(int acc, float c, float bias, bool has_bias, bool relu, uint32_t res_bits, bool has_res)
 {
@@ -259,60 +247,62 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
     // Scheduling hint for one half step (MI+NI fragment reads of the next half, MI*NI MFMAs of this
     // one): interleave the LDS reads with the MFMAs so the four waves of the workgroup do not hit
     // the LDS pipe in one burst.
-    auto interleave_hint = [&]() {
-        // one MFMA, one DS read, ...; the MFMAs left over close the half step, which gives the last
-        // read time to land before the next half step waits for it.
-        constexpr int READS = MI + NI, MFMAS = MI * NI;
+    auto interleave_hint = [&](auto NV) {
+        // one MFMA, one DS read (and, in the half step that refills a buffer, one global->LDS load)
+        // per group; the MFMAs left over close the half step, which gives the last read time to land
+        // before the next half step waits for it.
+        constexpr int READS = MI + NI, MFMAS = MI * NI, VMEM = decltype(NV)::value;
+        constexpr int GROUPS = READS > VMEM ? READS : VMEM;
 #pragma unroll
-        for (int r = 0; r < READS; ++r) {
+        for (int r = 0; r < GROUPS; ++r) {
             if (r < MFMAS) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (r < VMEM) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            if (r < READS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
-        if (MFMAS > READS) __builtin_amdgcn_sched_group_barrier(0x008, MFMAS - READS, 0);
+        if (MFMAS > GROUPS) __builtin_amdgcn_sched_group_barrier(0x008, MFMAS - GROUPS, 0);
     };
 
     // ---- pipeline prologue: stages 0 .. NSTAGE-2 in flight, stage 0 landed, first fragments read.
+    // Every K step issues exactly one stage of loads; past the end of the K range the last stage is
+    // simply fetched again into a buffer nobody reads.  That keeps the number of loads in flight
+    // constant (one immediate s_waitcnt value) and the loop body free of branches, so the loads and
+    // LDS reads can be interleaved with the MFMAs by the scheduler hints below.
 #pragma unroll
-    for (int s = 0; s < NSTAGE - 1; ++s)
-        if (s < nk) issue_stage(s, s);
+    for (int s = 0; s < NSTAGE - 1; ++s) issue_stage(s < nk ? s : nk - 1, s);
     if constexpr (BT) {
         // B stages 0 and 1 go through registers synchronously (which also drains the DMA loads above);
         // stage 2 stays in registers and is written to LDS during K step 0.
         load_b(0);
         store_b(0);
-        if (1 < nk) { load_b(1); store_b(1); }
-        if (2 < nk) load_b(2);
+        load_b(1 < nk ? 1 : nk - 1);
+        store_b(1);
+        load_b(2 < nk ? 2 : nk - 1);
         wait_vmcnt_imm<KR>();
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     } else {
-        const int inflight = nk < NSTAGE - 1 ? nk : NSTAGE - 1;
-        wait_stages<LPS, NSTAGE - 2>(inflight - 1);
+        wait_vmcnt_imm<(NSTAGE - 2) * LPS>();
     }
     __builtin_amdgcn_s_barrier();
     read_frags(fa0, fb0, 0, 0);
 
-    // Steady state: every K step but the last.  No LDS access is conditional here, so the compiler
-    // can wait on exactly the fragment reads an MFMA group needs.
     int buf = 0;
     for (int it = 0; it < nk - 1; ++it) {
         // first half of K step `it`
         read_frags(fa1, fb1, buf, 1);
         mfma_all(fa0, fb0);
-        interleave_hint();
+        interleave_hint(std::integral_constant<int, 0>{});
         // second half; meanwhile make stage it+1 visible and refill the buffer freed by step it-1
         const int nbuf = buf + 1 == NSTAGE ? 0 : buf + 1;
-        int last = it + NSTAGE - 2;
-        last = last < nk - 1 ? last : nk - 1;
-        wait_stages<LPS, NSTAGE - 3>(last - (it + 1));
+        wait_vmcnt_imm<(NSTAGE - 3) * LPS>();
         __builtin_amdgcn_s_barrier();
         if constexpr (BT) {
-            if (it + 2 < nk) store_b(buf + 2 >= NSTAGE ? buf + 2 - NSTAGE : buf + 2);
-            if (it + 3 < nk) load_b(it + 3);
+            store_b(buf + 2 >= NSTAGE ? buf + 2 - NSTAGE : buf + 2);
+            load_b(it + 3 < nk ? it + 3 : nk - 1);
         }
-        if (it + NSTAGE - 1 < nk) issue_stage(it + NSTAGE - 1, buf == 0 ? NSTAGE - 1 : buf - 1);
+        issue_stage(it + NSTAGE - 1 < nk ? it + NSTAGE - 1 : nk - 1, buf == 0 ? NSTAGE - 1 : buf - 1);
         read_frags(fa0, fb0, nbuf, 0);
         mfma_all(fa1, fb1);
-        interleave_hint();
+        interleave_hint(std::integral_constant<int, BT ? 0 : SA + SB>{});
         buf = nbuf;
     }
     // last K step
@@ -328,6 +318,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
     }
     mfma_all(fa0, fb0);
     mfma_all(fa1, fb1);
+    wait_vmcnt_imm<0>();  // the refills issued past the end of the K range have landed
 
     // ---- epilogue.  32x32 accumulator layout: lane l, register v holds
     // row 8*(v/4) + 4*(l>>5) + (v&3), column (l & 31).
@@ -463,14 +454,14 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs p, in
 
 // ---------------------------------------------------------------- host side: tile / split choice
 
+constexpr int kNumCU = 256;
+
 struct Plan {
-    int cfg;     // 0: 256x256 (prefill)  1: 128x256  2: 64x256  3: 32x256  4: 256x256 B^T  5: 256x128 B^T
+    int cfg;     // 0: 256x256 (prefill)  1: 128x256  2: 64x256  3: 32x256  4: 256x256 B^T  5: 256x128 B^T  6: 256x192
     int bm, bn;
     int splits, iters_per_split;
     int tiles_m, tiles_n;
 };
-
-constexpr int kNumCU = 256;
 
 Plan make_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split, bool b_transposed = false)
 {
@@ -482,7 +473,16 @@ Plan make_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split,
         else pl.cfg = 4;
         allow_split = false;
     }
-    else if (M > 128) { pl.cfg = 0; pl.bm = 256; }
+    else if (M > 128) {
+        // Compute-bound shapes: pick the tile width whose last round of tiles wastes the fewest CUs
+        // (rounds x tile width is proportional to the time); ties go to the wider tile.
+        pl.cfg = 0;
+        pl.bm = 256;
+        const int64_t tm = (M + 255) / 256;
+        const int64_t r256 = (tm * ((N + 255) / 256) * batch + kNumCU - 1) / kNumCU * 256;
+        const int64_t r192 = (tm * ((N + 191) / 192) * batch + kNumCU - 1) / kNumCU * 192;
+        if (r192 < r256) { pl.cfg = 6; pl.bn = 192; }
+    }
     else if (M > 64) { pl.cfg = 1; pl.bm = 128; }
     else if (M > 32) { pl.cfg = 2; pl.bm = 64; }
     else { pl.cfg = 3; pl.bm = 32; }
@@ -494,7 +494,7 @@ Plan make_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split,
         const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
         // Weight-streaming shapes: a few workgroups per CU keep every HBM channel busy.
         // Compute-bound shapes: split only to fill the last partial round of tiles.
-        const int64_t want = pl.cfg == 0 ? kNumCU : 2 * kNumCU;
+        const int64_t want = pl.bm == 256 ? kNumCU : 2 * kNumCU;
         if (tiles < want) {
             splits = (int)((want + tiles - 1) / tiles);
             const int max_splits = nk / 8 > 0 ? nk / 8 : 1;  // at least 8 K steps per split
@@ -518,6 +518,7 @@ void launch_cfg(const Plan& pl, const GemmArgs& a, int batch, hipStream_t st)
         case 1: hipLaunchKernelGGL((gemm_i8_kernel<128, 256, 1, 4, 6, EPI, BF16, false>), grid, dim3(256), 0, st, a); break;
         case 2: hipLaunchKernelGGL((gemm_i8_kernel<64, 256, 1, 4, 7, EPI, BF16, false>), grid, dim3(256), 0, st, a); break;
         case 3: hipLaunchKernelGGL((gemm_i8_kernel<32, 256, 1, 4, 8, EPI, BF16, false>), grid, dim3(256), 0, st, a); break;
+        case 6: hipLaunchKernelGGL((gemm_i8_kernel<256, 192, 2, 2, 4, EPI, BF16, false>), grid, dim3(256), 0, st, a); break;
         default:
             if constexpr (EPI == EPI_DEQUANT) {
                 if (pl.cfg == 4) hipLaunchKernelGGL((gemm_i8_kernel<256, 256, 2, 2, 4, EPI, BF16, true>), grid, dim3(256), 0, st, a);
