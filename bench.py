@@ -5,7 +5,8 @@ Workload (N=1): the four OPT-175B-shaped linears at hidden 12288 (QKV 12288->368
 12288->12288, FC1 12288->49152, FC2 49152->12288) at M = 2048 tokens, per-token dynamic activation
 quantization, per-tensor weights, bf16 output.  One step = for each of the four layers:
 quantize_act (fp16 activation -> int8 codes + per-token steps) then w8a8_linear (INT8 MFMA GEMM with
-the dequantizing epilogue fused).  Inputs (activations, prepared int8 weights) are resident in HBM
+the dequantizing epilogue fused); int8 operands use the library's tiled layout.  Inputs (activations,
+prepared int8 weights) are resident in HBM
 before the timed region.  Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -45,9 +46,9 @@ def make_layer(sq, torch, name, t, c_i, c_o, outlier_frac, factor, alpha, smooth
         aw = sq.weight_absmax_per_in_channel(w)
         s, inv_s = sq.smooth_scales(ax.cpu(), aw.cpu(), alpha)
         s_dev, inv_s_dev = s.cuda(), inv_s.cuda()
-    wq, w_scale = sq.prepare_weight(w, s_dev)
+    wq, w_scale = sq.prepare_weight(w, s_dev, layout=sq.TILED)
     del w
-    xq = torch.empty((t, c_i), dtype=torch.int8, device="cuda")
+    xq = sq.empty_codes(t, c_i, sq.TILED)
     x_scale = torch.empty(t, dtype=torch.float32, device="cuda")
     y = torch.empty((t, c_o), dtype=torch.bfloat16, device="cuda")
     nws = sq.workspace_bytes(sq.OP_W8A8_LINEAR, t, c_i, c_o)
@@ -57,8 +58,8 @@ def make_layer(sq, torch, name, t, c_i, c_o, outlier_frac, factor, alpha, smooth
 
 
 def run_layer(sq, torch, L):
-    sq.quantize_act(L["x"], sq.PER_TOKEN_DYNAMIC, inv_s=L["inv_s"], out=(L["xq"], L["x_scale"]))
-    sq.w8a8_linear(L["xq"], L["x_scale"], L["wq"], L["w_scale"], torch.bfloat16, out=L["y"], workspace=L["ws"])
+    sq.quantize_act(L["x"], sq.PER_TOKEN_DYNAMIC, inv_s=L["inv_s"], out=(L["xq"], L["x_scale"]), layout=sq.TILED)
+    sq.w8a8_linear(L["xq"], L["x_scale"], L["wq"], L["w_scale"], torch.bfloat16, out=L["y"], workspace=L["ws"], layout=sq.TILED)
 
 
 def cpu_baseline(layers_desc):
@@ -137,10 +138,10 @@ def main():
         a, b, c = (torch.cuda.Event(enable_timing=True) for _ in range(3))
         a.record()
         for _ in range(args.steps):
-            sq.quantize_act(L["x"], sq.PER_TOKEN_DYNAMIC, inv_s=L["inv_s"], out=(L["xq"], L["x_scale"]))
+            sq.quantize_act(L["x"], sq.PER_TOKEN_DYNAMIC, inv_s=L["inv_s"], out=(L["xq"], L["x_scale"]), layout=sq.TILED)
         b.record()
         for _ in range(args.steps):
-            sq.w8a8_linear(L["xq"], L["x_scale"], L["wq"], L["w_scale"], torch.bfloat16, out=L["y"], workspace=L["ws"])
+            sq.w8a8_linear(L["xq"], L["x_scale"], L["wq"], L["w_scale"], torch.bfloat16, out=L["y"], workspace=L["ws"], layout=sq.TILED)
         c.record()
         torch.cuda.synchronize()
         L["quant_us"] = a.elapsed_time(b) / args.steps * 1e3

@@ -51,6 +51,20 @@ typedef enum {
     SQ_PER_TENSOR_STATIC = 2   /* O3 */
 } sq_act_mode;
 
+/* Memory layout of an int8 GEMM operand with `rows` rows and k contraction elements.
+ *  SQ_ROW_MAJOR: [rows, k], k contiguous.
+ *  SQ_TILED:     the layout the GEMM streams fastest (every wave-wide load reads 1 KB of contiguous
+ *                memory).  Requires k % 64 == 0.  The buffer holds ceil(rows/16)*16 rows
+ *                (sq_tiled_bytes()); element (r, c) lives at byte
+ *                  ((r/16) * (k/64) + c/64) * 1024 + (r%16) * 64 + ((((c%64)/16) ^ sw) * 16) + c%16,
+ *                  sw = (((r%16) >> 1) & 3) ^ (((r%16) >> 3) & 1).
+ *                Rows beyond `rows` in the last block row are padding: never read as results, their
+ *                content is unspecified. */
+typedef enum { SQ_ROW_MAJOR = 0, SQ_TILED = 1 } sq_layout;
+
+/* Bytes of an int8 [rows, k] operand in SQ_TILED layout (k % 64 == 0), 0 on invalid arguments. */
+size_t sq_tiled_bytes(int64_t rows, int64_t k);
+
 typedef enum {
     SQ_OP_QUANTIZE_ACT = 0,
     SQ_OP_PREPARE_WEIGHT = 1,
@@ -81,10 +95,12 @@ sq_status sq_weight_absmax_per_in_channel(const void* w, sq_dtype dtype, int64_t
 /* Offline weight preparation (Eq. 3 then Eq. 1, per-tensor as in Table 2):
  *   W_hat = diag(s) W;  Delta_W = max|W_hat| / 127;  Wq = round(W_hat * fl32(127 / max|W_hat|)).
  * w: device [c_i, c_o] row-major 16-bit; s: device fp32 [c_i] or NULL (s = 1);
- * wq: device int8 [c_o, c_i] (transposed: contraction index contiguous); w_scale: device fp32 [1].
+ * wq: device int8 [c_o, c_i] (transposed: contraction index contiguous) in layout `wq_layout`;
+ * w_scale: device fp32 [1].
  * workspace: device, >= sq_workspace_bytes(SQ_OP_PREPARE_WEIGHT, ...) bytes. */
 sq_status sq_prepare_weight(const void* w, sq_dtype dtype, const float* s, int64_t c_i, int64_t c_o,
-                            int8_t* wq, float* w_scale, void* workspace, size_t ws_bytes, void* stream);
+                            int8_t* wq, sq_layout wq_layout, float* w_scale, void* workspace,
+                            size_t ws_bytes, void* stream);
 
 /* Activation quantization (Eq. 1; granularities of Table 2).
  * x: device [t, c_i] 16-bit, row stride ldx elements (ldx >= c_i, multiple of 8);
@@ -92,10 +108,11 @@ sq_status sq_prepare_weight(const void* w, sq_dtype dtype, const float* s, int64
  *   "extra scaling" for inputs whose producer cannot absorb 1/s, Sec. 4);
  * scale: device fp32; written in the dynamic modes ([t] per token, [1] per tensor), read in
  *   SQ_PER_TENSOR_STATIC ([1], the calibrated Delta);
- * xq: device int8 [t, c_i] packed;  workspace: device, needed for SQ_PER_TENSOR_DYNAMIC only. */
+ * xq: device int8 [t, c_i] in layout `xq_layout`;  workspace: device, needed for
+ *   SQ_PER_TENSOR_DYNAMIC only. */
 sq_status sq_quantize_act(const void* x, sq_dtype dtype, int64_t t, int64_t c_i, int64_t ldx,
                           const float* inv_s, sq_act_mode mode, float* scale, int8_t* xq,
-                          void* workspace, size_t ws_bytes, void* stream);
+                          sq_layout xq_layout, void* workspace, size_t ws_bytes, void* stream);
 
 /* W8A8 linear layer (Eq. 2) with the dequantizing epilogue fused into the INT8 GEMM:
  *   acc_tn = sum_j xq[t, j] * wq[n, j]                                   (exact int32)
@@ -104,17 +121,19 @@ sq_status sq_quantize_act(const void* x, sq_dtype dtype, int64_t t, int64_t c_i,
  * xq: device int8 [t, c_i]; x_scale: device fp32 [t] if x_scale_per_token else [1];
  * wq: device int8 [c_o, c_i]; w_scale: device fp32 [1];
  * bias: device fp32 [c_o] or NULL; residual: device [t, c_o] of the output dtype or NULL;
- * y: device [t, c_o] of dtype `out`.
+ * y: device [t, c_o] of dtype `out`, row-major.
+ * layout: layout of BOTH xq and wq (as produced by sq_quantize_act / sq_prepare_weight).
  * workspace: device, >= sq_workspace_bytes(SQ_OP_W8A8_LINEAR, t, c_i, c_o) bytes (may be 0). */
 sq_status sq_w8a8_linear(const int8_t* xq, const float* x_scale, int x_scale_per_token,
                          const int8_t* wq, const float* w_scale, const float* bias,
                          const void* residual, int relu, void* y, sq_dtype out, int64_t t,
-                         int64_t c_i, int64_t c_o, void* workspace, size_t ws_bytes, void* stream);
+                         int64_t c_i, int64_t c_o, sq_layout layout, void* workspace, size_t ws_bytes,
+                         void* stream);
 
 /* The raw integer contraction of Eq. 2 (test export: makes the bit-exact int32 gate observable).
- * acc: device int32 [t, c_o]. */
+ * acc: device int32 [t, c_o] row-major; layout: layout of both xq and wq. */
 sq_status sq_i8_gemm_i32(const int8_t* xq, const int8_t* wq, int32_t* acc, int64_t t, int64_t c_i,
-                         int64_t c_o, void* workspace, size_t ws_bytes, void* stream);
+                         int64_t c_o, sq_layout layout, void* workspace, size_t ws_bytes, void* stream);
 
 /* INT8 batched matmul of attention (Sec. 4): c[b] = round_to_16bit( fl32( float(a[b] B[b]) * alpha ) ).
  * a: device int8 [b, m, k]; bm: device int8, [b, n, k] if trans_b (Q K^T) else [b, k, n] (P V);
@@ -135,9 +154,10 @@ sq_status sq_softmax_quant_p(const void* s, sq_dtype dtype, int64_t rows, int64_
  * beta_f = beta / s, folded offline as Sec. 4 describes) fused with per-token dynamic quantization:
  *   x_hat_tj = (x_tj - mean_t) * rstd_t * gamma_f_j + beta_f_j;  then Eq. 1 per token.
  * x: device [t, c_i] 16-bit packed; gamma_f, beta_f: device fp32 [c_i]; scale: device fp32 [t];
- * xq: device int8 [t, c_i]. */
+ * xq: device int8 [t, c_i] in layout `xq_layout`. */
 sq_status sq_ln_quantize(const void* x, sq_dtype dtype, int64_t t, int64_t c_i, const float* gamma_f,
-                         const float* beta_f, float eps, float* scale, int8_t* xq, void* stream);
+                         const float* beta_f, float eps, float* scale, int8_t* xq, sq_layout xq_layout,
+                         void* stream);
 
 /* Workspace size in bytes for `op` at the given problem size (0 if none is needed).  For
  * SQ_OP_W8A8_BMM pass (m, k, n) as (t, c_i, c_o). */

@@ -18,11 +18,12 @@ LIB_PATH = os.path.join(_HERE, "libsqmi.so")
 F16, BF16 = 0, 1
 PER_TOKEN_DYNAMIC, PER_TENSOR_DYNAMIC, PER_TENSOR_STATIC = 0, 1, 2
 OP_QUANTIZE_ACT, OP_PREPARE_WEIGHT, OP_W8A8_LINEAR, OP_I8_GEMM_I32, OP_W8A8_BMM = range(5)
+ROW_MAJOR, TILED = 0, 1
 
 EXPORTS = (
     "sq_status_string", "sq_smooth_scales", "sq_act_absmax_per_channel", "sq_weight_absmax_per_in_channel",
     "sq_prepare_weight", "sq_quantize_act", "sq_w8a8_linear", "sq_i8_gemm_i32", "sq_w8a8_bmm",
-    "sq_softmax_quant_p", "sq_ln_quantize", "sq_workspace_bytes",
+    "sq_softmax_quant_p", "sq_ln_quantize", "sq_workspace_bytes", "sq_tiled_bytes",
 )
 
 
@@ -47,15 +48,17 @@ def lib() -> ctypes.CDLL:
         L.sq_smooth_scales.argtypes = [vp, vp, f32, i64, vp, vp]
         L.sq_act_absmax_per_channel.argtypes = [vp, i32, i64, i64, vp, vp]
         L.sq_weight_absmax_per_in_channel.argtypes = [vp, i32, i64, i64, vp, vp]
-        L.sq_prepare_weight.argtypes = [vp, i32, vp, i64, i64, vp, vp, vp, ctypes.c_size_t, vp]
-        L.sq_quantize_act.argtypes = [vp, i32, i64, i64, i64, vp, i32, vp, vp, vp, ctypes.c_size_t, vp]
-        L.sq_w8a8_linear.argtypes = [vp, vp, i32, vp, vp, vp, vp, i32, vp, i32, i64, i64, i64, vp, ctypes.c_size_t, vp]
-        L.sq_i8_gemm_i32.argtypes = [vp, vp, vp, i64, i64, i64, vp, ctypes.c_size_t, vp]
+        L.sq_prepare_weight.argtypes = [vp, i32, vp, i64, i64, vp, i32, vp, vp, ctypes.c_size_t, vp]
+        L.sq_quantize_act.argtypes = [vp, i32, i64, i64, i64, vp, i32, vp, vp, i32, vp, ctypes.c_size_t, vp]
+        L.sq_w8a8_linear.argtypes = [vp, vp, i32, vp, vp, vp, vp, i32, vp, i32, i64, i64, i64, i32, vp, ctypes.c_size_t, vp]
+        L.sq_i8_gemm_i32.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, ctypes.c_size_t, vp]
         L.sq_w8a8_bmm.argtypes = [vp, vp, i32, f32, vp, i32, i64, i64, i64, i64, i64, i64, i64, vp]
         L.sq_softmax_quant_p.argtypes = [vp, i32, i64, i64, vp, vp]
-        L.sq_ln_quantize.argtypes = [vp, i32, i64, i64, vp, vp, f32, vp, vp, vp]
+        L.sq_ln_quantize.argtypes = [vp, i32, i64, i64, vp, vp, f32, vp, vp, i32, vp]
         L.sq_workspace_bytes.restype = ctypes.c_size_t
         L.sq_workspace_bytes.argtypes = [i32, i64, i64, i64]
+        L.sq_tiled_bytes.restype = ctypes.c_size_t
+        L.sq_tiled_bytes.argtypes = [i64, i64]
         for name in EXPORTS:
             getattr(L, name)
         _lib = L
@@ -107,6 +110,17 @@ def _workspace(nbytes: int, device, workspace):
     return workspace.data_ptr(), workspace.numel() * workspace.element_size(), workspace
 
 
+def empty_codes(rows: int, k: int, layout: int = ROW_MAJOR, device="cuda") -> torch.Tensor:
+    """int8 [rows, k] operand buffer.  In the TILED layout the storage is padded to a multiple of 16 rows
+    and the returned tensor is the [rows, k] view of it (its bytes are in tiled order, not row order)."""
+    if layout == TILED:
+        nbytes = int(lib().sq_tiled_bytes(rows, k))
+        if nbytes == 0:
+            raise SqmiError("tiled layout needs k % 64 == 0")
+        return torch.empty((nbytes // k, k), dtype=torch.int8, device=device)[:rows]
+    return torch.empty((rows, k), dtype=torch.int8, device=device)
+
+
 def smooth_scales(x_absmax: torch.Tensor, w_absmax: torch.Tensor, alpha: float):
     """Eq. 4 on HOST fp32 tensors -> (s, inv_s) host fp32 tensors."""
     xa = x_absmax.detach().to("cpu", torch.float32).contiguous()
@@ -134,24 +148,24 @@ def weight_absmax_per_in_channel(w: torch.Tensor) -> torch.Tensor:
     return out
 
 
-def prepare_weight(w: torch.Tensor, s: torch.Tensor | None = None, workspace=None):
-    """W [c_i, c_o] (+ optional device fp32 s [c_i]) -> (wq int8 [c_o, c_i], w_scale fp32 [1])."""
+def prepare_weight(w: torch.Tensor, s: torch.Tensor | None = None, workspace=None, layout: int = ROW_MAJOR):
+    """W [c_i, c_o] (+ optional device fp32 s [c_i]) -> (wq int8 [c_o, c_i] in `layout`, w_scale fp32 [1])."""
     c_i, c_o = w.shape
-    wq = torch.empty((c_o, c_i), dtype=torch.int8, device=w.device)
+    wq = empty_codes(c_o, c_i, layout, w.device)
     w_scale = torch.empty(1, dtype=torch.float32, device=w.device)
     wp, wb, keep = _workspace(workspace_bytes(OP_PREPARE_WEIGHT, 0, c_i, c_o), w.device, workspace)
     _check(lib().sq_prepare_weight(_dev(w, None, "w"), _dt(w), _opt(s, torch.float32, "s"), c_i, c_o, wq.data_ptr(),
-                                   w_scale.data_ptr(), wp, wb, _stream()), "sq_prepare_weight")
+                                   layout, w_scale.data_ptr(), wp, wb, _stream()), "sq_prepare_weight")
     return wq, w_scale
 
 
 def quantize_act(x: torch.Tensor, mode: int, inv_s: torch.Tensor | None = None, static_scale: torch.Tensor | None = None,
-                 c_i: int | None = None, out=None, workspace=None):
+                 c_i: int | None = None, out=None, workspace=None, layout: int = ROW_MAJOR):
     """x [t, ldx] -> (xq int8 [t, c_i], scale fp32 [t] or [1]).  ``c_i`` < ldx quantizes a column prefix."""
     t, ldx = x.shape
     c_i = ldx if c_i is None else c_i
     if out is None:
-        xq = torch.empty((t, c_i), dtype=torch.int8, device=x.device)
+        xq = empty_codes(t, c_i, layout, x.device)
         if mode == PER_TENSOR_STATIC:
             if static_scale is None:
                 raise SqmiError("static mode needs static_scale")
@@ -163,13 +177,14 @@ def quantize_act(x: torch.Tensor, mode: int, inv_s: torch.Tensor | None = None, 
     wp, wb, keep = _workspace(workspace_bytes(OP_QUANTIZE_ACT, t, c_i, 0) if mode == PER_TENSOR_DYNAMIC else 0,
                               x.device, workspace)
     _check(lib().sq_quantize_act(_dev(x, None, "x"), _dt(x), t, c_i, ldx, _opt(inv_s, torch.float32, "inv_s"), mode,
-                                 _dev(scale, torch.float32, "scale"), _dev(xq, torch.int8, "xq"), wp, wb, _stream()),
-           "sq_quantize_act")
+                                 _dev(scale, torch.float32, "scale"), _dev(xq, torch.int8, "xq"), layout, wp, wb,
+                                 _stream()), "sq_quantize_act")
     return xq, scale
 
 
 def w8a8_linear(xq: torch.Tensor, x_scale: torch.Tensor, wq: torch.Tensor, w_scale: torch.Tensor, out_dtype,
-                bias=None, residual=None, relu: bool = False, out=None, workspace=None) -> torch.Tensor:
+                bias=None, residual=None, relu: bool = False, out=None, workspace=None,
+                layout: int = ROW_MAJOR) -> torch.Tensor:
     t, c_i = xq.shape
     c_o = wq.shape[0]
     if wq.shape[1] != c_i:
@@ -182,17 +197,18 @@ def w8a8_linear(xq: torch.Tensor, x_scale: torch.Tensor, wq: torch.Tensor, w_sca
     _check(lib().sq_w8a8_linear(_dev(xq, torch.int8, "xq"), _dev(x_scale, torch.float32, "x_scale"), per_token,
                                 _dev(wq, torch.int8, "wq"), _dev(w_scale, torch.float32, "w_scale"),
                                 _opt(bias, torch.float32, "bias"), _opt(residual, out_dtype, "residual"), int(relu),
-                                _dev(y, out_dtype, "y"), _dt(y), t, c_i, c_o, wp, wb, _stream()), "sq_w8a8_linear")
+                                _dev(y, out_dtype, "y"), _dt(y), t, c_i, c_o, layout, wp, wb, _stream()),
+           "sq_w8a8_linear")
     return y
 
 
-def i8_gemm_i32(xq: torch.Tensor, wq: torch.Tensor, workspace=None) -> torch.Tensor:
+def i8_gemm_i32(xq: torch.Tensor, wq: torch.Tensor, workspace=None, layout: int = ROW_MAJOR) -> torch.Tensor:
     t, c_i = xq.shape
     c_o = wq.shape[0]
     acc = torch.empty((t, c_o), dtype=torch.int32, device=xq.device)
     wp, wb, keep = _workspace(workspace_bytes(OP_I8_GEMM_I32, t, c_i, c_o), xq.device, workspace)
     _check(lib().sq_i8_gemm_i32(_dev(xq, torch.int8, "xq"), _dev(wq, torch.int8, "wq"), acc.data_ptr(), t, c_i, c_o,
-                                wp, wb, _stream()), "sq_i8_gemm_i32")
+                                layout, wp, wb, _stream()), "sq_i8_gemm_i32")
     return acc
 
 
@@ -215,14 +231,15 @@ def softmax_quant_p(s: torch.Tensor, out=None) -> torch.Tensor:
     return pq
 
 
-def ln_quantize(x: torch.Tensor, gamma_f: torch.Tensor, beta_f: torch.Tensor, eps: float = 1e-5, out=None):
+def ln_quantize(x: torch.Tensor, gamma_f: torch.Tensor, beta_f: torch.Tensor, eps: float = 1e-5, out=None,
+                layout: int = ROW_MAJOR):
     t, c_i = x.shape
     if out is None:
-        xq = torch.empty((t, c_i), dtype=torch.int8, device=x.device)
+        xq = empty_codes(t, c_i, layout, x.device)
         scale = torch.empty(t, dtype=torch.float32, device=x.device)
     else:
         xq, scale = out
     _check(lib().sq_ln_quantize(_dev(x, None, "x"), _dt(x), t, c_i, _dev(gamma_f, torch.float32, "gamma_f"),
                                 _dev(beta_f, torch.float32, "beta_f"), eps, _dev(scale, torch.float32, "scale"),
-                                _dev(xq, torch.int8, "xq"), _stream()), "sq_ln_quantize")
+                                _dev(xq, torch.int8, "xq"), layout, _stream()), "sq_ln_quantize")
     return xq, scale

@@ -42,6 +42,12 @@ sq_status sq_smooth_scales(const float* x_absmax, const float* w_absmax, float a
     return SQ_OK;
 }
 
+size_t sq_tiled_bytes(int64_t rows, int64_t k)
+{
+    if (rows <= 0 || k <= 0 || (k & 63)) return 0;
+    return (size_t)((rows + 15) / 16 * 16) * (size_t)k;
+}
+
 size_t sq_workspace_bytes(sq_op op, int64_t t, int64_t c_i, int64_t c_o)
 {
     switch (op) {

@@ -41,6 +41,19 @@ SQ_DEVICE int round_code(float v)
     return (int)r;
 }
 
+// Byte offset of element (r, c) of an int8 [rows, k] operand in the SQ_TILED layout (see sqmi.h).
+SQ_DEVICE int64_t tiled_offset(int64_t r, int c, int k)
+{
+    const int rr = (int)(r & 15);
+    const int sw = ((rr >> 1) & 3) ^ ((rr >> 3) & 1);
+    return ((r >> 4) * (int64_t)(k >> 6) + (c >> 6)) * 1024 + rr * 64 + ((((c >> 4) & 3) ^ sw) << 4) + (c & 15);
+}
+// Destination of the codes starting at column c of row r (c % 8 == 0: 8 codes never straddle a chunk).
+SQ_DEVICE int8_t* code_dst(int8_t* base, int64_t r, int c, int k, bool tiled)
+{
+    return base + (tiled ? tiled_offset(r, c, k) : r * (int64_t)k + c);
+}
+
 // Wave-wide max over 64 lanes (all lanes receive the result).
 SQ_DEVICE float wave_max(float v)
 {

@@ -65,9 +65,21 @@ SQ_DEVICE uint32_t dequant_one(int acc, float c, float bias, bool has_bias, bool
 // BT = false: B is [N, K] (K-contiguous rows, like A).  BT = true: B is [K, N] (the V operand of
 // attention's P V product): its tiles are read through registers, transposed bytewise in registers
 // and written to the same LDS layout, so the MFMA loop is identical.
-template <int BM, int BN, int WGM, int WGN, int NSTAGE, int EPI, bool BF16, bool BT>
+//
+// LAY selects the operand layouts in global memory:
+//   LAY_ROWS  A [M, K] and B [N, K] row-major (K contiguous);
+//   LAY_BT    A row-major, B [K, N] (transposed, see above);
+//   LAY_TILED A and B in the tiled layout of sq_layout SQ_TILED: 16-row x 64-byte blocks of 1 KB,
+//             stored block-row-major, each block an exact image of the LDS block (chunk permutation
+//             included).  One wave-wide load then copies 1 KB of contiguous global memory -- eight whole
+//             128-byte lines instead of sixteen 64-byte row segments -- which is what the L2 -> CU path
+//             serves best.
+enum { LAY_ROWS = 0, LAY_BT = 1, LAY_TILED = 2 };
+
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, int EPI, bool BF16, int LAY>
 __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArgs p)
 {
+    constexpr bool BT = LAY == LAY_BT, TILED = LAY == LAY_TILED;
     constexpr int NW = WGM * WGN, BK = 64;
     constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
     constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE = A_BYTES + B_BYTES;
@@ -118,9 +130,11 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
     const int nk = (nk_total - kbeg) < p.iters_per_split ? (nk_total - kbeg) : p.iters_per_split;
     const int tail_chunks = (p.K & (BK - 1)) >> 4;  // valid 16-byte chunks of the last K step (0 = all 4)
 
-    const int8_t* Ab = p.A + (int64_t)batch * p.strideA + (int64_t)m0 * p.lda + (int64_t)kbeg * BK;
+    // Tiled operands: a 16-row block row is 16*K contiguous bytes and a K step advances 1 KB.
+    constexpr int KSTEP = TILED ? 1024 : BK;
+    const int8_t* Ab = p.A + (int64_t)batch * p.strideA + (int64_t)m0 * p.lda + (int64_t)kbeg * KSTEP;
     const int8_t* Bb = BT ? p.B + (int64_t)batch * p.strideB + n0
-                          : p.B + (int64_t)batch * p.strideB + (int64_t)n0 * p.ldb + (int64_t)kbeg * BK;
+                          : p.B + (int64_t)batch * p.strideB + (int64_t)n0 * p.ldb + (int64_t)kbeg * KSTEP;
 
     // ---- global -> LDS load slots of this wave.  Slot i moves 16-row block (i*NW + wave), 1 KB per
     // stage.  Lane l lands at LDS byte l*16 of the block, i.e. the block is row-major (64 B per row),
@@ -134,19 +148,29 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
 #pragma unroll
     for (int i = 0; i < SA; ++i) {
         const int rb = (i * NW + wave) % RBA;  // wraps only when RBA is not a multiple of NW: a benign duplicate
-        int row = rb * 16 + (lane >> 2);
-        const int last = p.M - 1 - m0;
-        row = row < last ? row : last;
-        offA[i] = (uint32_t)(row * (int)p.lda + chunk * 16);
+        if constexpr (TILED) {
+            const int last_rb = (p.M - 1 - m0) >> 4;  // ragged M: re-read the last valid block row
+            offA[i] = (uint32_t)((rb < last_rb ? rb : last_rb) * 16 * (int)p.lda + lane * 16);
+        } else {
+            int row = rb * 16 + (lane >> 2);
+            const int last = p.M - 1 - m0;
+            row = row < last ? row : last;
+            offA[i] = (uint32_t)(row * (int)p.lda + chunk * 16);
+        }
         ldsA[i] = rb * 1024;
     }
 #pragma unroll
     for (int i = 0; i < SB; ++i) {
         const int rb = (i * NW + wave) % RBB;
-        int row = rb * 16 + (lane >> 2);
-        const int last = p.N - 1 - n0;
-        row = row < last ? row : last;
-        offB[i] = (uint32_t)(row * (int)p.ldb + chunk * 16);
+        if constexpr (TILED) {
+            const int last_rb = (p.N - 1 - n0) >> 4;
+            offB[i] = (uint32_t)((rb < last_rb ? rb : last_rb) * 16 * (int)p.ldb + lane * 16);
+        } else {
+            int row = rb * 16 + (lane >> 2);
+            const int last = p.N - 1 - n0;
+            row = row < last ? row : last;
+            offB[i] = (uint32_t)(row * (int)p.ldb + chunk * 16);
+        }
         ldsB[i] = A_BYTES + rb * 1024;
     }
 
@@ -154,8 +178,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
     // re-read chunk 0 (valid memory); their A fragments are zeroed in registers before the MFMAs.
     const bool has_tail = tail_chunks != 0 && (kbeg + nk == nk_total);
     auto issue_stage = [&](int kt, int buf) {
-        const int8_t* a = Ab + (int64_t)kt * BK;
-        const int8_t* b = Bb + (int64_t)kt * BK;
+        const int8_t* a = Ab + (int64_t)kt * KSTEP;
+        const int8_t* b = Bb + (int64_t)kt * KSTEP;
         char* base = smem + buf * STAGE;
         const uint32_t back = (has_tail && kt == nk - 1 && chunk >= tail_chunks) ? (uint32_t)chunk * 16u : 0u;
 #pragma unroll
@@ -510,26 +534,32 @@ Plan make_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split,
 }
 
 template <int EPI, bool BF16>
-void launch_cfg(const Plan& pl, const GemmArgs& a, int batch, hipStream_t st)
+void launch_cfg(const Plan& pl, const GemmArgs& a, int batch, hipStream_t st, bool tiled)
 {
     dim3 grid((unsigned)(pl.tiles_m * pl.tiles_n * pl.splits), (unsigned)batch);
+#define SQ_LAUNCH(BM, BN, WGM, WGN, NST)                                                                          \
+    do {                                                                                                          \
+        if (tiled) hipLaunchKernelGGL((gemm_i8_kernel<BM, BN, WGM, WGN, NST, EPI, BF16, LAY_TILED>), grid, dim3(256), 0, st, a); \
+        else hipLaunchKernelGGL((gemm_i8_kernel<BM, BN, WGM, WGN, NST, EPI, BF16, LAY_ROWS>), grid, dim3(256), 0, st, a);        \
+    } while (0)
     switch (pl.cfg) {
-        case 0: hipLaunchKernelGGL((gemm_i8_kernel<256, 256, 2, 2, 4, EPI, BF16, false>), grid, dim3(256), 0, st, a); break;
-        case 1: hipLaunchKernelGGL((gemm_i8_kernel<128, 256, 1, 4, 6, EPI, BF16, false>), grid, dim3(256), 0, st, a); break;
-        case 2: hipLaunchKernelGGL((gemm_i8_kernel<64, 256, 1, 4, 7, EPI, BF16, false>), grid, dim3(256), 0, st, a); break;
-        case 3: hipLaunchKernelGGL((gemm_i8_kernel<32, 256, 1, 4, 8, EPI, BF16, false>), grid, dim3(256), 0, st, a); break;
-        case 6: hipLaunchKernelGGL((gemm_i8_kernel<256, 192, 2, 2, 4, EPI, BF16, false>), grid, dim3(256), 0, st, a); break;
+        case 0: SQ_LAUNCH(256, 256, 2, 2, 4); break;
+        case 1: SQ_LAUNCH(128, 256, 1, 4, 6); break;
+        case 2: SQ_LAUNCH(64, 256, 1, 4, 7); break;
+        case 3: SQ_LAUNCH(32, 256, 1, 4, 8); break;
+        case 6: SQ_LAUNCH(256, 192, 2, 2, 4); break;
         default:
             if constexpr (EPI == EPI_DEQUANT) {
-                if (pl.cfg == 4) hipLaunchKernelGGL((gemm_i8_kernel<256, 256, 2, 2, 4, EPI, BF16, true>), grid, dim3(256), 0, st, a);
-                else hipLaunchKernelGGL((gemm_i8_kernel<256, 128, 4, 1, 5, EPI, BF16, true>), grid, dim3(256), 0, st, a);
+                if (pl.cfg == 4) hipLaunchKernelGGL((gemm_i8_kernel<256, 256, 2, 2, 4, EPI, BF16, LAY_BT>), grid, dim3(256), 0, st, a);
+                else hipLaunchKernelGGL((gemm_i8_kernel<256, 128, 4, 1, 5, EPI, BF16, LAY_BT>), grid, dim3(256), 0, st, a);
             }
             break;
     }
+#undef SQ_LAUNCH
 }
 
 sq_status run_gemm(GemmArgs a, int64_t batch, bool to_i32, bool bf16, void* workspace, size_t ws_bytes, hipStream_t st,
-                   bool b_transposed = false)
+                   bool b_transposed = false, bool tiled = false)
 {
     Plan pl = make_plan(a.M, a.N, a.K, batch, true, b_transposed);
     a.tiles_m = pl.tiles_m;
@@ -541,7 +571,7 @@ sq_status run_gemm(GemmArgs a, int64_t batch, bool to_i32, bool bf16, void* work
         if (!workspace || ws_bytes < need) return SQ_ERR_WORKSPACE;
         void* final_out = to_i32 ? (void*)a.acc_out : a.C;
         a.acc_out = (int32_t*)workspace;
-        launch_cfg<EPI_I32, false>(pl, a, 1, st);
+        launch_cfg<EPI_I32, false>(pl, a, 1, st, tiled);
         a.C = final_out;
         const int64_t total = (int64_t)a.M * a.N;
         int blocks = (int)((total + 255) / 256);
@@ -549,11 +579,11 @@ sq_status run_gemm(GemmArgs a, int64_t batch, bool to_i32, bool bf16, void* work
         if (bf16) hipLaunchKernelGGL(splitk_reduce_kernel<true>, dim3(blocks), dim3(256), 0, st, a, to_i32 ? 1 : 0);
         else hipLaunchKernelGGL(splitk_reduce_kernel<false>, dim3(blocks), dim3(256), 0, st, a, to_i32 ? 1 : 0);
     } else if (to_i32) {
-        launch_cfg<EPI_I32, false>(pl, a, (int)batch, st);
+        launch_cfg<EPI_I32, false>(pl, a, (int)batch, st, tiled);
     } else if (bf16) {
-        launch_cfg<EPI_DEQUANT, true>(pl, a, (int)batch, st);
+        launch_cfg<EPI_DEQUANT, true>(pl, a, (int)batch, st, tiled);
     } else {
-        launch_cfg<EPI_DEQUANT, false>(pl, a, (int)batch, st);
+        launch_cfg<EPI_DEQUANT, false>(pl, a, (int)batch, st, tiled);
     }
     return sq_launch_status();
 }
@@ -578,12 +608,14 @@ size_t sq_gemm_workspace_bytes(int64_t t, int64_t c_i, int64_t c_o)
 
 sq_status sq_w8a8_linear(const int8_t* xq, const float* x_scale, int x_scale_per_token, const int8_t* wq,
                          const float* w_scale, const float* bias, const void* residual, int relu, void* y,
-                         sq_dtype out, int64_t t, int64_t c_i, int64_t c_o, void* workspace, size_t ws_bytes,
-                         void* stream)
+                         sq_dtype out, int64_t t, int64_t c_i, int64_t c_o, sq_layout layout, void* workspace,
+                         size_t ws_bytes, void* stream)
 {
     if (!xq || !x_scale || !wq || !w_scale || !y) return SQ_ERR_NULL;
     if (!dims_ok(t, c_i, c_o)) return SQ_ERR_SHAPE;
     if (out != SQ_F16 && out != SQ_BF16) return SQ_ERR_UNSUPPORTED;
+    if (layout != SQ_ROW_MAJOR && layout != SQ_TILED) return SQ_ERR_UNSUPPORTED;
+    if (layout == SQ_TILED && (c_i & 63)) return SQ_ERR_ALIGN;
     if ((c_i & 15) || !sq_aligned16(xq) || !sq_aligned16(wq) || !sq_aligned16(y) ||
         (residual && !sq_aligned16(residual)) || (workspace && !sq_aligned16(workspace)))
         return SQ_ERR_ALIGN;
@@ -593,14 +625,16 @@ sq_status sq_w8a8_linear(const int8_t* xq, const float* x_scale, int x_scale_per
     a.lda = c_i; a.ldb = c_i;
     a.C = y; a.x_scale = x_scale; a.per_token = x_scale_per_token ? 1 : 0; a.w_scale = w_scale;
     a.bias = bias; a.residual = residual; a.relu = relu ? 1 : 0;
-    return run_gemm(a, 1, false, out == SQ_BF16, workspace, ws_bytes, (hipStream_t)stream);
+    return run_gemm(a, 1, false, out == SQ_BF16, workspace, ws_bytes, (hipStream_t)stream, false, layout == SQ_TILED);
 }
 
 sq_status sq_i8_gemm_i32(const int8_t* xq, const int8_t* wq, int32_t* acc, int64_t t, int64_t c_i, int64_t c_o,
-                         void* workspace, size_t ws_bytes, void* stream)
+                         sq_layout layout, void* workspace, size_t ws_bytes, void* stream)
 {
     if (!xq || !wq || !acc) return SQ_ERR_NULL;
     if (!dims_ok(t, c_i, c_o)) return SQ_ERR_SHAPE;
+    if (layout != SQ_ROW_MAJOR && layout != SQ_TILED) return SQ_ERR_UNSUPPORTED;
+    if (layout == SQ_TILED && (c_i & 63)) return SQ_ERR_ALIGN;
     if ((c_i & 15) || !sq_aligned16(xq) || !sq_aligned16(wq) || !sq_aligned16(acc) ||
         (workspace && !sq_aligned16(workspace)))
         return SQ_ERR_ALIGN;
@@ -610,7 +644,7 @@ sq_status sq_i8_gemm_i32(const int8_t* xq, const int8_t* wq, int32_t* acc, int64
     a.lda = c_i; a.ldb = c_i;
     a.acc_out = acc;
     a.C = acc;
-    return run_gemm(a, 1, true, false, workspace, ws_bytes, (hipStream_t)stream);
+    return run_gemm(a, 1, true, false, workspace, ws_bytes, (hipStream_t)stream, false, layout == SQ_TILED);
 }
 
 // Attention BMM dispatcher behind sq_w8a8_bmm (arguments already validated).

@@ -63,7 +63,7 @@ SQ_DEVICE float block_max_256(float v, float* red)
 template <bool BF16, int NV>
 __global__ __launch_bounds__(256) void quant_per_token_block(const uint16_t* __restrict__ x, int64_t ldx, int c_i,
                                                             const float* __restrict__ inv_s, float* __restrict__ scale,
-                                                            int8_t* __restrict__ xq)
+                                                            int8_t* __restrict__ xq, bool tiled)
 {
     __shared__ float red[4];
     const int64_t row = blockIdx.x;
@@ -87,7 +87,6 @@ __global__ __launch_bounds__(256) void quant_per_token_block(const uint16_t* __r
     const float a = block_max_256(m, red);
     const float r = a > 0.0f ? 127.0f / a : 0.0f;
     if (threadIdx.x == 0) scale[row] = a / 127.0f;
-    v2u* out = (v2u*)(xq + row * (int64_t)c_i);
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const int idx = threadIdx.x + i * 256;
@@ -95,7 +94,7 @@ __global__ __launch_bounds__(256) void quant_per_token_block(const uint16_t* __r
             float f[8];
             unpack8<BF16>(raw[i], f);
             if (inv_s) smooth8(f, inv_s, idx * 8);
-            __builtin_nontemporal_store(quant8(f, r), out + idx);
+            __builtin_nontemporal_store(quant8(f, r), (v2u*)code_dst(xq, row, idx * 8, c_i, tiled));
         }
     }
 }
@@ -104,7 +103,7 @@ __global__ __launch_bounds__(256) void quant_per_token_block(const uint16_t* __r
 template <bool BF16, int NV>
 __global__ __launch_bounds__(256) void quant_per_token_wave(const uint16_t* __restrict__ x, int64_t ldx, int c_i, int64_t t,
                                                            const float* __restrict__ inv_s, float* __restrict__ scale,
-                                                           int8_t* __restrict__ xq)
+                                                           int8_t* __restrict__ xq, bool tiled)
 {
     const int lane = threadIdx.x & 63;
     const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -129,7 +128,6 @@ __global__ __launch_bounds__(256) void quant_per_token_wave(const uint16_t* __re
     const float a = wave_max(m);
     const float r = a > 0.0f ? 127.0f / a : 0.0f;
     if (lane == 0) scale[row] = a / 127.0f;
-    v2u* out = (v2u*)(xq + row * (int64_t)c_i);
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const int idx = lane + i * 64;
@@ -137,7 +135,7 @@ __global__ __launch_bounds__(256) void quant_per_token_wave(const uint16_t* __re
             float f[8];
             unpack8<BF16>(raw[i], f);
             if (inv_s) smooth8(f, inv_s, idx * 8);
-            out[idx] = quant8(f, r);
+            *(v2u*)code_dst(xq, row, idx * 8, c_i, tiled) = quant8(f, r);
         }
     }
 }
@@ -147,7 +145,7 @@ __global__ __launch_bounds__(256) void quant_per_token_wave(const uint16_t* __re
 template <bool BF16>
 __global__ __launch_bounds__(256) void quant_per_token_stream(const uint16_t* __restrict__ x, int64_t ldx, int c_i,
                                                              const float* __restrict__ inv_s, float* __restrict__ scale,
-                                                             int8_t* __restrict__ xq)
+                                                             int8_t* __restrict__ xq, bool tiled)
 {
     __shared__ float red[4];
     const int64_t row = blockIdx.x;
@@ -163,12 +161,11 @@ __global__ __launch_bounds__(256) void quant_per_token_stream(const uint16_t* __
     const float a = block_max_256(m, red);
     const float r = a > 0.0f ? 127.0f / a : 0.0f;
     if (threadIdx.x == 0) scale[row] = a / 127.0f;
-    v2u* out = (v2u*)(xq + row * (int64_t)c_i);
     for (int idx = threadIdx.x; idx < nvec; idx += 256) {
         float f[8];
         unpack8<BF16>(xr[idx], f);
         if (inv_s) smooth8(f, inv_s, idx * 8);
-        out[idx] = quant8(f, r);
+        *(v2u*)code_dst(xq, row, idx * 8, c_i, tiled) = quant8(f, r);
     }
 }
 
@@ -207,7 +204,7 @@ __global__ __launch_bounds__(256) void tensor_absmax_kernel(const uint16_t* __re
 template <bool BF16, bool DYNAMIC>
 __global__ __launch_bounds__(256) void quant_per_tensor_kernel(const uint16_t* __restrict__ x, int64_t ldx, int c_i, int64_t t,
                                                               const float* __restrict__ inv_s, float* scale,
-                                                              const uint32_t* amax_bits, int8_t* __restrict__ xq)
+                                                              const uint32_t* amax_bits, int8_t* __restrict__ xq, bool tiled)
 {
     float r;
     if (DYNAMIC) {
@@ -226,7 +223,7 @@ __global__ __launch_bounds__(256) void quant_per_tensor_kernel(const uint16_t* _
         float f[8];
         unpack8<BF16>(__builtin_nontemporal_load((const v4u*)(x + row * ldx) + idx), f);
         if (inv_s) smooth8(f, inv_s, idx * 8);
-        __builtin_nontemporal_store(quant8(f, r), (v2u*)(xq + row * (int64_t)c_i) + idx);
+        __builtin_nontemporal_store(quant8(f, r), (v2u*)code_dst(xq, row, idx * 8, c_i, tiled));
     }
 }
 
@@ -251,11 +248,11 @@ __global__ __launch_bounds__(256) void act_absmax_per_channel_kernel(const uint1
 
 template <bool BF16>
 void launch_per_token(const uint16_t* x, int64_t ldx, int c_i, int64_t t, const float* inv_s, float* scale, int8_t* xq,
-                      hipStream_t st)
+                      bool tiled, hipStream_t st)
 {
     const int nvec = c_i >> 3;
-#define SQ_WAVE(NV) hipLaunchKernelGGL((quant_per_token_wave<BF16, NV>), dim3((unsigned)((t + 3) / 4)), dim3(256), 0, st, x, ldx, c_i, t, inv_s, scale, xq)
-#define SQ_BLOCK(NV) hipLaunchKernelGGL((quant_per_token_block<BF16, NV>), dim3((unsigned)t), dim3(256), 0, st, x, ldx, c_i, inv_s, scale, xq)
+#define SQ_WAVE(NV) hipLaunchKernelGGL((quant_per_token_wave<BF16, NV>), dim3((unsigned)((t + 3) / 4)), dim3(256), 0, st, x, ldx, c_i, t, inv_s, scale, xq, tiled)
+#define SQ_BLOCK(NV) hipLaunchKernelGGL((quant_per_token_block<BF16, NV>), dim3((unsigned)t), dim3(256), 0, st, x, ldx, c_i, inv_s, scale, xq, tiled)
     if (nvec <= 64) SQ_WAVE(1);
     else if (nvec <= 128) SQ_WAVE(2);
     else if (nvec <= 256) SQ_BLOCK(1);
@@ -267,7 +264,7 @@ void launch_per_token(const uint16_t* x, int64_t ldx, int c_i, int64_t t, const 
     else if (nvec <= 4096) SQ_BLOCK(16);
     else if (nvec <= 6144) SQ_BLOCK(24);
     else if (nvec <= 8192) SQ_BLOCK(32);
-    else hipLaunchKernelGGL((quant_per_token_stream<BF16>), dim3((unsigned)t), dim3(256), 0, st, x, ldx, c_i, inv_s, scale, xq);
+    else hipLaunchKernelGGL((quant_per_token_stream<BF16>), dim3((unsigned)t), dim3(256), 0, st, x, ldx, c_i, inv_s, scale, xq, tiled);
 #undef SQ_WAVE
 #undef SQ_BLOCK
 }
@@ -284,13 +281,17 @@ int grid_for(int64_t work_items)
 extern "C" {
 
 sq_status sq_quantize_act(const void* x, sq_dtype dtype, int64_t t, int64_t c_i, int64_t ldx, const float* inv_s,
-                          sq_act_mode mode, float* scale, int8_t* xq, void* workspace, size_t ws_bytes, void* stream)
+                          sq_act_mode mode, float* scale, int8_t* xq, sq_layout xq_layout, void* workspace,
+                          size_t ws_bytes, void* stream)
 {
     if (!x || !scale || !xq) return SQ_ERR_NULL;
     if (t <= 0 || c_i <= 0 || ldx < c_i || t >= ((int64_t)1 << 31) || c_i >= ((int64_t)1 << 31)) return SQ_ERR_SHAPE;
     if (dtype != SQ_F16 && dtype != SQ_BF16) return SQ_ERR_UNSUPPORTED;
     if (mode != SQ_PER_TOKEN_DYNAMIC && mode != SQ_PER_TENSOR_DYNAMIC && mode != SQ_PER_TENSOR_STATIC)
         return SQ_ERR_UNSUPPORTED;
+    if (xq_layout != SQ_ROW_MAJOR && xq_layout != SQ_TILED) return SQ_ERR_UNSUPPORTED;
+    if (xq_layout == SQ_TILED && (c_i & 63)) return SQ_ERR_ALIGN;
+    const bool tiled = xq_layout == SQ_TILED;
     if ((c_i & 15) || (ldx & 7) || !sq_aligned16(x) || !sq_aligned16(xq) || (inv_s && !sq_aligned16(inv_s)))
         return SQ_ERR_ALIGN;
     if (mode == SQ_PER_TENSOR_DYNAMIC && (!workspace || ws_bytes < sizeof(uint32_t))) return SQ_ERR_WORKSPACE;
@@ -298,8 +299,8 @@ sq_status sq_quantize_act(const void* x, sq_dtype dtype, int64_t t, int64_t c_i,
     const uint16_t* xp = (const uint16_t*)x;
     const bool bf = dtype == SQ_BF16;
     if (mode == SQ_PER_TOKEN_DYNAMIC) {
-        if (bf) launch_per_token<true>(xp, ldx, (int)c_i, t, inv_s, scale, xq, st);
-        else launch_per_token<false>(xp, ldx, (int)c_i, t, inv_s, scale, xq, st);
+        if (bf) launch_per_token<true>(xp, ldx, (int)c_i, t, inv_s, scale, xq, tiled, st);
+        else launch_per_token<false>(xp, ldx, (int)c_i, t, inv_s, scale, xq, tiled, st);
         return sq_launch_status();
     }
     const int grid = grid_for(t * (c_i >> 3));
@@ -308,14 +309,14 @@ sq_status sq_quantize_act(const void* x, sq_dtype dtype, int64_t t, int64_t c_i,
         hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, st, amax, 0u, 1);
         if (bf) {
             hipLaunchKernelGGL(tensor_absmax_kernel<true>, dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, amax);
-            hipLaunchKernelGGL((quant_per_tensor_kernel<true, true>), dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, amax, xq);
+            hipLaunchKernelGGL((quant_per_tensor_kernel<true, true>), dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, amax, xq, tiled);
         } else {
             hipLaunchKernelGGL(tensor_absmax_kernel<false>, dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, amax);
-            hipLaunchKernelGGL((quant_per_tensor_kernel<false, true>), dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, amax, xq);
+            hipLaunchKernelGGL((quant_per_tensor_kernel<false, true>), dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, amax, xq, tiled);
         }
     } else {
-        if (bf) hipLaunchKernelGGL((quant_per_tensor_kernel<true, false>), dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, (const uint32_t*)nullptr, xq);
-        else hipLaunchKernelGGL((quant_per_tensor_kernel<false, false>), dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, (const uint32_t*)nullptr, xq);
+        if (bf) hipLaunchKernelGGL((quant_per_tensor_kernel<true, false>), dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, (const uint32_t*)nullptr, xq, tiled);
+        else hipLaunchKernelGGL((quant_per_tensor_kernel<false, false>), dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, (const uint32_t*)nullptr, xq, tiled);
     }
     return sq_launch_status();
 }

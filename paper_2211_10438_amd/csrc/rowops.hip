@@ -94,7 +94,7 @@ __global__ __launch_bounds__(256) void softmax_quant_kernel(const uint16_t* __re
 template <bool BF16, int NV>
 __global__ __launch_bounds__(256) void ln_quant_kernel(const uint16_t* __restrict__ x, int c_i, const float* __restrict__ gamma_f,
                                                       const float* __restrict__ beta_f, float eps, float* __restrict__ scale,
-                                                      int8_t* __restrict__ xq)
+                                                      int8_t* __restrict__ xq, bool tiled)
 {
     __shared__ float red[4];
     const int64_t row = blockIdx.x;
@@ -145,7 +145,6 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(const uint16_t* __restric
     const float a = block_max_r(m, red);
     const float r = a > 0.0f ? 127.0f / a : 0.0f;
     if (threadIdx.x == 0) scale[row] = a / 127.0f;
-    v2u* out = (v2u*)(xq + row * (int64_t)c_i);
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const int idx = threadIdx.x + i * 256;
@@ -153,7 +152,7 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(const uint16_t* __restric
             int q[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) q[e] = round_code(f[i][e] * r);
-            __builtin_nontemporal_store(pack8(q), out + idx);
+            __builtin_nontemporal_store(pack8(q), (v2u*)code_dst(xq, row, idx * 8, c_i, tiled));
         }
     }
 }
@@ -183,18 +182,21 @@ sq_status sq_softmax_quant_p(const void* s, sq_dtype dtype, int64_t rows, int64_
 }
 
 sq_status sq_ln_quantize(const void* x, sq_dtype dtype, int64_t t, int64_t c_i, const float* gamma_f, const float* beta_f,
-                         float eps, float* scale, int8_t* xq, void* stream)
+                         float eps, float* scale, int8_t* xq, sq_layout xq_layout, void* stream)
 {
     if (!x || !gamma_f || !beta_f || !scale || !xq) return SQ_ERR_NULL;
     if (t <= 0 || c_i <= 0 || t >= ((int64_t)1 << 31)) return SQ_ERR_SHAPE;
     if (dtype != SQ_F16 && dtype != SQ_BF16) return SQ_ERR_UNSUPPORTED;
     if (c_i > 8 * 256 * 8) return SQ_ERR_UNSUPPORTED;  // hidden sizes up to 16384
+    if (xq_layout != SQ_ROW_MAJOR && xq_layout != SQ_TILED) return SQ_ERR_UNSUPPORTED;
+    if (xq_layout == SQ_TILED && (c_i & 63)) return SQ_ERR_ALIGN;
+    const bool tiled = xq_layout == SQ_TILED;
     if ((c_i & 15) || !sq_aligned16(x) || !sq_aligned16(xq) || !sq_aligned16(gamma_f) || !sq_aligned16(beta_f))
         return SQ_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
     const int nvec = (int)(c_i >> 3);
     const uint16_t* xp = (const uint16_t*)x;
-#define SQ_LN(BF, NV) hipLaunchKernelGGL((ln_quant_kernel<BF, NV>), dim3((unsigned)t), dim3(256), 0, st, xp, (int)c_i, gamma_f, beta_f, eps, scale, xq)
+#define SQ_LN(BF, NV) hipLaunchKernelGGL((ln_quant_kernel<BF, NV>), dim3((unsigned)t), dim3(256), 0, st, xp, (int)c_i, gamma_f, beta_f, eps, scale, xq, tiled)
     if (dtype == SQ_BF16) {
         if (nvec <= 256) SQ_LN(true, 1); else if (nvec <= 512) SQ_LN(true, 2); else if (nvec <= 1024) SQ_LN(true, 4); else SQ_LN(true, 8);
     } else {

@@ -59,7 +59,7 @@ template <bool BF16>
 __global__ __launch_bounds__(256) void weight_quant_transpose_kernel(const uint16_t* __restrict__ w, int c_i, int c_o,
                                                                     const float* __restrict__ s,
                                                                     const uint32_t* amax_bits, float* w_scale,
-                                                                    int8_t* __restrict__ wq)
+                                                                    int8_t* __restrict__ wq, bool tiled)
 {
     __shared__ __attribute__((aligned(16))) int8_t tileT[64][80];  // [n][j], padded pitch
     const float a = __builtin_bit_cast(float, *amax_bits);
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void weight_quant_transpose_kernel(const uint1
         const int nl = threadIdx.x >> 2, jc = (threadIdx.x & 3) * 16;
         const int n = n0 + nl, j = j0 + jc;
         if (n < c_o && j < c_i)  // c_i % 16 == 0
-            *(v4u*)(wq + (int64_t)n * c_i + j) = *(const v4u*)&tileT[nl][jc];
+            *(v4u*)code_dst(wq, n, j, c_i, tiled) = *(const v4u*)&tileT[nl][jc];  // 16 codes = one chunk
     }
 }
 
@@ -108,12 +108,15 @@ sq_status sq_weight_absmax_per_in_channel(const void* w, sq_dtype dtype, int64_t
 }
 
 sq_status sq_prepare_weight(const void* w, sq_dtype dtype, const float* s, int64_t c_i, int64_t c_o, int8_t* wq,
-                            float* w_scale, void* workspace, size_t ws_bytes, void* stream)
+                            sq_layout wq_layout, float* w_scale, void* workspace, size_t ws_bytes, void* stream)
 {
     if (!w || !wq || !w_scale) return SQ_ERR_NULL;
     if (c_i <= 0 || c_o <= 0 || c_i >= ((int64_t)1 << 31) || c_o >= ((int64_t)1 << 31)) return SQ_ERR_SHAPE;
     if (dtype != SQ_F16 && dtype != SQ_BF16) return SQ_ERR_UNSUPPORTED;
+    if (wq_layout != SQ_ROW_MAJOR && wq_layout != SQ_TILED) return SQ_ERR_UNSUPPORTED;
     if ((c_i & 15) || (c_o & 7) || !sq_aligned16(w) || !sq_aligned16(wq)) return SQ_ERR_ALIGN;
+    if (wq_layout == SQ_TILED && (c_i & 63)) return SQ_ERR_ALIGN;
+    const bool tiled = wq_layout == SQ_TILED;
     if (!workspace || ws_bytes < sizeof(uint32_t)) return SQ_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     uint32_t* amax = (uint32_t*)workspace;
@@ -122,10 +125,10 @@ sq_status sq_prepare_weight(const void* w, sq_dtype dtype, const float* s, int64
     dim3 grid2((unsigned)((c_o + 63) / 64), (unsigned)((c_i + 63) / 64));
     if (dtype == SQ_BF16) {
         hipLaunchKernelGGL(weight_row_absmax_kernel<true>, dim3(grid1), dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, (float*)nullptr, amax);
-        hipLaunchKernelGGL(weight_quant_transpose_kernel<true>, grid2, dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, amax, w_scale, wq);
+        hipLaunchKernelGGL(weight_quant_transpose_kernel<true>, grid2, dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, amax, w_scale, wq, tiled);
     } else {
         hipLaunchKernelGGL(weight_row_absmax_kernel<false>, dim3(grid1), dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, (float*)nullptr, amax);
-        hipLaunchKernelGGL(weight_quant_transpose_kernel<false>, grid2, dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, amax, w_scale, wq);
+        hipLaunchKernelGGL(weight_quant_transpose_kernel<false>, grid2, dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, amax, w_scale, wq, tiled);
     }
     return sq_launch_status();
 }

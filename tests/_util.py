@@ -41,3 +41,30 @@ def random_bf16_bits(shape, seed, scale=1.0):
 
 def torch_dtype(dt: int):
     return torch.float16 if dt == F16 else torch.bfloat16
+
+
+def tiled_index(rows: int, k: int) -> np.ndarray:
+    """Byte offset of element (r, c) of an int8 [rows, k] operand in the library's TILED layout,
+    written from the formula in include/sqmi.h (index plumbing for the tests, no method arithmetic)."""
+    r = np.arange(rows, dtype=np.int64)[:, None]
+    c = np.arange(k, dtype=np.int64)[None, :]
+    rr = r % 16
+    sw = ((rr >> 1) & 3) ^ ((rr >> 3) & 1)
+    return ((r // 16) * (k // 64) + c // 64) * 1024 + rr * 64 + ((((c % 64) // 16) ^ sw) * 16) + c % 16
+
+
+def tiled_to_rows(t: torch.Tensor) -> np.ndarray:
+    """Logical [rows, k] codes of a tensor returned by the binding in TILED layout."""
+    rows, k = t.shape
+    base = t._base if t._base is not None else t
+    raw = base.cpu().numpy().reshape(-1)
+    return raw[tiled_index(rows, k)]
+
+
+def rows_to_tiled_dev(codes: np.ndarray) -> torch.Tensor:
+    """Upload row-major codes in TILED layout; returns the [rows, k] view the binding expects."""
+    rows, k = codes.shape
+    pad = (rows + 15) // 16 * 16
+    raw = np.zeros(pad * k, np.int8)
+    raw[tiled_index(rows, k).reshape(-1)] = codes.reshape(-1)
+    return torch.from_numpy(raw.reshape(pad, k)).cuda()[:rows]
