@@ -6,7 +6,9 @@
 // accumulators while they are still in registers.
 //
 // Design (CDNA4):
-//  * v_mfma_i32_32x32x32_i8, one wave owns a (MI*32) x (NI*32) block of accumulators.
+//  * v_mfma_i32_32x32x32_i8, one wave owns a (MI*32) x (NI*32) block of accumulators; the prefill
+//    tiles (256x256, 256x192) run 8 waves = 2 per SIMD, so one wave's barrier / LDS waits are
+//    covered by the other wave's MFMAs.
 //  * Operand tiles travel HBM -> LDS with global_load_lds_dwordx4 (no VGPR staging), NSTAGE deep.
 //    LDS holds a tile as 16-row blocks of 1 KB, row-major (64 B per row) with the four 16-byte
 //    K-chunks of a row XOR-permuted: (a) one wave-wide load instruction fills a block from 16 rows
@@ -539,15 +541,15 @@ void launch_cfg(const Plan& pl, const GemmArgs& a, int batch, hipStream_t st, bo
     dim3 grid((unsigned)(pl.tiles_m * pl.tiles_n * pl.splits), (unsigned)batch);
 #define SQ_LAUNCH(BM, BN, WGM, WGN, NST)                                                                          \
     do {                                                                                                          \
-        if (tiled) hipLaunchKernelGGL((gemm_i8_kernel<BM, BN, WGM, WGN, NST, EPI, BF16, LAY_TILED>), grid, dim3(256), 0, st, a); \
-        else hipLaunchKernelGGL((gemm_i8_kernel<BM, BN, WGM, WGN, NST, EPI, BF16, LAY_ROWS>), grid, dim3(256), 0, st, a);        \
+        if (tiled) hipLaunchKernelGGL((gemm_i8_kernel<BM, BN, WGM, WGN, NST, EPI, BF16, LAY_TILED>), grid, dim3(WGM * WGN * 64), 0, st, a); \
+        else hipLaunchKernelGGL((gemm_i8_kernel<BM, BN, WGM, WGN, NST, EPI, BF16, LAY_ROWS>), grid, dim3(WGM * WGN * 64), 0, st, a); \
     } while (0)
     switch (pl.cfg) {
-        case 0: SQ_LAUNCH(256, 256, 2, 2, 4); break;
+        case 0: SQ_LAUNCH(256, 256, 2, 4, 4); break;
         case 1: SQ_LAUNCH(128, 256, 1, 4, 6); break;
         case 2: SQ_LAUNCH(64, 256, 1, 4, 7); break;
         case 3: SQ_LAUNCH(32, 256, 1, 4, 8); break;
-        case 6: SQ_LAUNCH(256, 192, 2, 2, 4); break;
+        case 6: SQ_LAUNCH(256, 192, 4, 2, 4); break;
         default:
             if constexpr (EPI == EPI_DEQUANT) {
                 if (pl.cfg == 4) hipLaunchKernelGGL((gemm_i8_kernel<256, 256, 2, 2, 4, EPI, BF16, LAY_BT>), grid, dim3(256), 0, st, a);
