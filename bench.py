@@ -92,6 +92,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--tokens", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--probe", action="store_true",
+                    help="counter probe for rocprofv3 --pmc: a 512 MiB device copy (known size) and two steps of the "
+                         "workload, nothing timed, no JSON")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one MI355X per box); --gpus must be 1. "
@@ -116,6 +119,16 @@ def main():
     def step():
         for L in layers:
             run_layer(sq, torch, L)
+
+    if args.probe:
+        src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda").random_()
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            dst.copy_(src)
+            step()
+        torch.cuda.synchronize()
+        print("probe done: copy of %d bytes + 2 steps" % src.numel())
+        return
 
     for _ in range(args.warmup):
         step()
@@ -151,6 +164,14 @@ def main():
     gemm_tops = total_ops / (gemm_ms * 1e-3) / 1e12
     quant_bytes = sum(3.0 * L["t"] * L["c_i"] + 4.0 * L["t"] for L in layers)
 
+    # HBM-side traffic of the GEMM launches: measured separately with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on
+    # `bench.py --probe` (counters cannot be read from inside this process); the summary is kept under profiles/.
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "gemm_i8_opt175b_M2048_hbm_traffic.json")
+    if t == 2048 and os.path.exists(tpath):
+        with open(tpath) as fh:
+            traffic = round(json.load(fh)["gemm_traffic_bytes_per_launch_avg"])
+
     out = {
         "metric": "W8A8 quant+GEMM+dequant TOPS and % INT8 MFMA peak at OPT-175B layer shapes",
         "value": round(tops, 2),
@@ -167,11 +188,12 @@ def main():
         "config": {"workload": f"opt175b_linears_hidden12288_M{t}: qkv+out_proj+fc1+fc2, per-token dynamic act, "
                                "per-tensor weight, bf16 out, 0.5% outlier channels x80, alpha 0.5"},
         "pct_int8_mfma_peak": round(100.0 * tops / PEAK_INT8_TOPS, 2),
-        "roofline": {"bound": "mfma", "kernel": "gemm_i8_kernel<256,256,2,2,4> (INT8 MFMA GEMM + dequant epilogue)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_i8_kernel (256x256 / 256x192 tiles, INT8 MFMA GEMM + dequant epilogue)",
                      "achieved": round(gemm_tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s",
-                     "frac": round(gemm_tops / PEAK_INT8_TOPS, 4), "traffic": None,
+                     "frac": round(gemm_tops / PEAK_INT8_TOPS, 4), "traffic": traffic,
                      "note": "int8 multiply-accumulate counted as 2 ops; achieved = sum of 2*T*C_i*C_o over the four "
-                             "layers / sum of their average GEMM launch durations (HIP events)"},
+                             "layers / sum of their average GEMM launch durations (HIP events); traffic = HBM-side "
+                             "bytes (FETCH_SIZE + WRITE_SIZE, calibrated on a copy) averaged over the four launches"},
         "per_layer_us": {L["name"]: {"quantize": round(L["quant_us"], 1), "gemm": round(L["gemm_us"], 1),
                                      "gemm_tops": round(L["ops"] / L["gemm_us"] / 1e6, 1)} for L in layers},
         "quantize_pass": {"bound": "hbm", "achieved_GBs": round(quant_bytes / (quant_ms * 1e-3) / 1e9, 1),

@@ -50,50 +50,66 @@ SQ_DEVICE v2u quant8(const float (&f)[8], float r)
     return out;
 }
 
-// Block-wide max for a 256-thread workgroup.
-SQ_DEVICE float block_max_256(float v, float* red)
+// Block-wide max for a workgroup of NT threads (NT / 64 waves).
+template <int NT> SQ_DEVICE float block_max(float v, float* red)
 {
     v = wave_max(v);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
     __syncthreads();
-    return __builtin_fmaxf(__builtin_fmaxf(red[0], red[1]), __builtin_fmaxf(red[2], red[3]));
+    float m = red[0];
+#pragma unroll
+    for (int w = 1; w < NT / 64; ++w) m = __builtin_fmaxf(m, red[w]);
+    return m;
 }
+SQ_DEVICE float block_max_256(float v, float* red) { return block_max<256>(v, red); }
 
-// One row per 256-thread workgroup; NV 16-byte vectors (8 elements) per thread kept in registers.
-template <bool BF16, int NV>
-__global__ __launch_bounds__(256) void quant_per_token_block(const uint16_t* __restrict__ x, int64_t ldx, int c_i,
-                                                            const float* __restrict__ inv_s, float* __restrict__ scale,
-                                                            int8_t* __restrict__ xq, bool tiled)
+// One row per workgroup of NT threads; NV 16-byte vectors (8 elements) per thread kept in registers.
+// KEEP: the smoothed fp32 values stay in registers between the two phases (worth it while NV is small);
+// otherwise x * inv_s is evaluated again in the second phase -- the same fp32 product, hence the same code.
+template <bool BF16, int NV, int NT, bool KEEP>
+__global__ __launch_bounds__(NT) void quant_per_token_block(const uint16_t* __restrict__ x, int64_t ldx, int c_i,
+                                                           const float* __restrict__ inv_s, float* __restrict__ scale,
+                                                           int8_t* __restrict__ xq, bool tiled)
 {
-    __shared__ float red[4];
+    __shared__ float red[NT / 64];
     const int64_t row = blockIdx.x;
     const v4u* xr = (const v4u*)(x + row * ldx);
     const int nvec = c_i >> 3;
     v4u raw[NV];
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-        const int idx = threadIdx.x + i * 256;
+        const int idx = threadIdx.x + i * NT;
         raw[i] = idx < nvec ? __builtin_nontemporal_load(xr + idx) : v4u{0, 0, 0, 0};
     }
+    float kept[KEEP ? NV : 1][8];
     float m = 0.0f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-        const int idx = threadIdx.x + i * 256;
+        const int idx = threadIdx.x + i * NT;
         float f[8];
         unpack8<BF16>(raw[i], f);
         if (inv_s && idx < nvec) smooth8(f, inv_s, idx * 8);
         m = __builtin_fmaxf(m, absmax8(f));
+        if constexpr (KEEP) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) kept[i][e] = f[e];
+        }
     }
-    const float a = block_max_256(m, red);
+    const float a = block_max<NT>(m, red);
     const float r = a > 0.0f ? 127.0f / a : 0.0f;
     if (threadIdx.x == 0) scale[row] = a / 127.0f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-        const int idx = threadIdx.x + i * 256;
+        const int idx = threadIdx.x + i * NT;
         if (idx < nvec) {
             float f[8];
-            unpack8<BF16>(raw[i], f);
-            if (inv_s) smooth8(f, inv_s, idx * 8);
+            if constexpr (KEEP) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) f[e] = kept[i][e];
+            } else {
+                unpack8<BF16>(raw[i], f);
+                if (inv_s) smooth8(f, inv_s, idx * 8);
+            }
             __builtin_nontemporal_store(quant8(f, r), (v2u*)code_dst(xq, row, idx * 8, c_i, tiled));
         }
     }
@@ -252,18 +268,21 @@ void launch_per_token(const uint16_t* x, int64_t ldx, int c_i, int64_t t, const 
 {
     const int nvec = c_i >> 3;
 #define SQ_WAVE(NV) hipLaunchKernelGGL((quant_per_token_wave<BF16, NV>), dim3((unsigned)((t + 3) / 4)), dim3(256), 0, st, x, ldx, c_i, t, inv_s, scale, xq, tiled)
-#define SQ_BLOCK(NV) hipLaunchKernelGGL((quant_per_token_block<BF16, NV>), dim3((unsigned)t), dim3(256), 0, st, x, ldx, c_i, inv_s, scale, xq, tiled)
+#define SQ_BLOCK(NV, NT)                                                                                                        \
+    do {                                                                                                                        \
+        if (inv_s && NV <= 8) hipLaunchKernelGGL((quant_per_token_block<BF16, NV, NT, true>), dim3((unsigned)t), dim3(NT), 0, st, x, ldx, c_i, inv_s, scale, xq, tiled); \
+        else hipLaunchKernelGGL((quant_per_token_block<BF16, NV, NT, false>), dim3((unsigned)t), dim3(NT), 0, st, x, ldx, c_i, inv_s, scale, xq, tiled);                 \
+    } while (0)
     if (nvec <= 64) SQ_WAVE(1);
     else if (nvec <= 128) SQ_WAVE(2);
-    else if (nvec <= 256) SQ_BLOCK(1);
-    else if (nvec <= 512) SQ_BLOCK(2);
-    else if (nvec <= 1024) SQ_BLOCK(4);
-    else if (nvec <= 1536) SQ_BLOCK(6);
-    else if (nvec <= 2048) SQ_BLOCK(8);
-    else if (nvec <= 3072) SQ_BLOCK(12);
-    else if (nvec <= 4096) SQ_BLOCK(16);
-    else if (nvec <= 6144) SQ_BLOCK(24);
-    else if (nvec <= 8192) SQ_BLOCK(32);
+    else if (nvec <= 256) SQ_BLOCK(1, 256);
+    else if (nvec <= 512) SQ_BLOCK(2, 256);
+    else if (nvec <= 1024) SQ_BLOCK(4, 256);
+    else if (nvec <= 1536) SQ_BLOCK(6, 256);
+    else if (nvec <= 2048) SQ_BLOCK(8, 256);
+    else if (nvec <= 4096) SQ_BLOCK(4, 1024);
+    else if (nvec <= 6144) SQ_BLOCK(6, 1024);
+    else if (nvec <= 8192) SQ_BLOCK(8, 1024);
     else hipLaunchKernelGGL((quant_per_token_stream<BF16>), dim3((unsigned)t), dim3(256), 0, st, x, ldx, c_i, inv_s, scale, xq, tiled);
 #undef SQ_WAVE
 #undef SQ_BLOCK
