@@ -1,0 +1,45 @@
+// Argument block and epilogue arithmetic shared by the INT8 GEMM kernels (gfx950).
+#pragma once
+#include "common.h"
+
+#define GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+struct GemmArgs {
+    const int8_t* A;  // [batch][M, K], row stride lda bytes
+    const int8_t* B;  // [batch][N, K], row stride ldb bytes
+    int M, N, K;
+    int64_t lda, ldb;
+    int64_t strideA, strideB, strideC;  // batch strides in elements
+    int tiles_m, tiles_n, splits, iters_per_split;
+    // dequant epilogue
+    void* C;  // [batch][M, N] 16-bit, row stride N
+    const float* x_scale;  // [M] or [1] or NULL (then `alpha` is the whole scale)
+    int per_token;
+    const float* w_scale;  // [1]
+    float alpha;
+    const float* bias;     // [N] or NULL
+    const void* residual;  // [M, N] out dtype or NULL
+    int relu;
+    // int32 output (raw accumulators or split-K partials): [splits][M, N]
+    int32_t* acc_out;
+};
+
+template <int N> SQ_DEVICE void wait_vmcnt_imm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+// Outer-dimension scaling of Eq. 2 on one accumulator: (float)acc * c, then the optional terms in the
+// order bias, ReLU, residual, then one rounding to the 16-bit output type.
+template <bool BF16>
+SQ_DEVICE uint32_t dequant_one(int acc, float c, float bias, bool has_bias, bool relu, uint32_t res_bits, bool has_res)
+{
+    float v = (float)acc * c;
+    if (has_bias) v = v + bias;
+    if (relu) v = v > 0.0f ? v : 0.0f;
+    if (has_res) v = v + load16_bits<BF16>(res_bits);
+    return store16_bits<BF16>(v);
+}
+
+// Weight-streaming GEMM for few-token shapes (gemm_i8_stream.hip).  Returns false when the shape is
+// not one it balances well; nothing is launched then.
+bool sq_stream_gemm_eligible(int64_t M, int64_t N, int64_t K, int64_t batch);
+void sq_stream_gemm_launch(const GemmArgs& a, bool to_i32, bool bf16, bool tiled, hipStream_t st);

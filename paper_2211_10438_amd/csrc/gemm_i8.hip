@@ -22,46 +22,11 @@
 //    second small kernel that also runs the epilogue.
 #include <type_traits>
 
-#include "common.h"
-
-#define GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
-#define LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+#include "gemm_args.h"
 
 namespace {
 
 enum { EPI_DEQUANT = 0, EPI_I32 = 1 };
-
-struct GemmArgs {
-    const int8_t* A;  // [batch][M, K], row stride lda bytes
-    const int8_t* B;  // [batch][N, K], row stride ldb bytes
-    int M, N, K;
-    int64_t lda, ldb;
-    int64_t strideA, strideB, strideC;  // batch strides in elements
-    int tiles_m, tiles_n, splits, iters_per_split;
-    // dequant epilogue
-    void* C;  // [batch][M, N] 16-bit, row stride N
-    const float* x_scale;  // [M] or [1] or NULL (then `alpha` is the whole scale)
-    int per_token;
-    const float* w_scale;  // [1]
-    float alpha;
-    const float* bias;     // [N] or NULL
-    const void* residual;  // [M, N] out dtype or NULL
-    int relu;
-    // int32 output (raw accumulators or split-K partials): [splits][M, N]
-    int32_t* acc_out;
-};
-
-template <int N> SQ_DEVICE void wait_vmcnt_imm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
-
-template <bool BF16>
-SQ_DEVICE uint32_t dequant_one(int acc, float c, float bias, bool has_bias, bool relu, uint32_t res_bits, bool has_res)
-{
-    float v = (float)acc * c;
-    if (has_bias) v = v + bias;
-    if (relu) v = v > 0.0f ? v : 0.0f;
-    if (has_res) v = v + load16_bits<BF16>(res_bits);
-    return store16_bits<BF16>(v);
-}
 
 // BM x BN output tile per workgroup, WGM x WGN waves, BK = 64 bytes of K per pipeline stage.
 // BT = false: B is [N, K] (K-contiguous rows, like A).  BT = true: B is [K, N] (the V operand of
@@ -563,6 +528,11 @@ void launch_cfg(const Plan& pl, const GemmArgs& a, int batch, hipStream_t st, bo
 sq_status run_gemm(GemmArgs a, int64_t batch, bool to_i32, bool bf16, void* workspace, size_t ws_bytes, hipStream_t st,
                    bool b_transposed = false, bool tiled = false)
 {
+    if (!b_transposed && sq_stream_gemm_eligible(a.M, a.N, a.K, batch)) {
+        // few tokens, wide C_o: stream W once through one workgroup per CU (no split-K, no workspace)
+        sq_stream_gemm_launch(a, to_i32, bf16, tiled, st);
+        return sq_launch_status();
+    }
     Plan pl = make_plan(a.M, a.N, a.K, batch, true, b_transposed);
     a.tiles_m = pl.tiles_m;
     a.tiles_n = pl.tiles_n;
@@ -604,6 +574,7 @@ extern "C" {
 size_t sq_gemm_workspace_bytes(int64_t t, int64_t c_i, int64_t c_o)
 {
     if (!dims_ok(t, c_i, c_o)) return 0;
+    if (sq_stream_gemm_eligible(t, c_o, c_i, 1)) return 0;
     Plan pl = make_plan(t, c_o, c_i, 1, true);
     return pl.splits > 1 ? (size_t)pl.splits * t * c_o * sizeof(int32_t) : 0;
 }

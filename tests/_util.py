@@ -62,9 +62,16 @@ def tiled_to_rows(t: torch.Tensor) -> np.ndarray:
 
 
 def rows_to_tiled_dev(codes: np.ndarray) -> torch.Tensor:
-    """Upload row-major codes in TILED layout; returns the [rows, k] view the binding expects."""
+    """Upload row-major codes in TILED layout; returns the [rows, k] view the binding expects.
+    Block-wise (16 rows x 64 columns -> 1 KB, the four 16-byte chunks of row r stored at chunk ^ sw(r)):
+    the same layout as tiled_index, built with reshapes so that large operands stay cheap."""
     rows, k = codes.shape
     pad = (rows + 15) // 16 * 16
-    raw = np.zeros(pad * k, np.int8)
-    raw[tiled_index(rows, k).reshape(-1)] = codes.reshape(-1)
-    return torch.from_numpy(raw.reshape(pad, k)).cuda()[:rows]
+    full = np.zeros((pad, k), np.int8)
+    full[:rows] = codes
+    blk = full.reshape(pad // 16, 16, k // 64, 4, 16).transpose(0, 2, 1, 3, 4)  # [R/16, K/64, row, chunk, byte]
+    rr = np.arange(16)
+    sw = ((rr >> 1) & 3) ^ ((rr >> 3) & 1)
+    src_chunk = np.arange(4)[None, :] ^ sw[:, None]  # stored position p of row r holds chunk p ^ sw(r)
+    out = blk[:, :, rr[:, None], src_chunk, :]
+    return torch.from_numpy(np.ascontiguousarray(out).reshape(pad, k)).cuda()[:rows]

@@ -71,10 +71,12 @@ def test_argument_validation_happens_before_any_launch():
     assert L.sq_w8a8_linear(fake, fake, 1, fake, fake, NULL, NULL, 0, fake, 0, 4, 40, 64, 0, NULL, 0, NULL) == 3
     assert L.sq_w8a8_linear(fake, fake, 1, fake, fake, NULL, NULL, 0, fake, 0, 4, 80, 64, 1, NULL, 0, NULL) == 3  # tiled: c_i % 64
     assert L.sq_w8a8_linear(fake, fake, 1, fake, fake, NULL, NULL, 0, fake, 5, 4, 64, 64, 0, NULL, 0, NULL) == 4
-    # a split-K shape without workspace
-    need = L.sq_workspace_bytes(sq.OP_W8A8_LINEAR, 16, 12288, 12288)
+    # a split-K shape (few tokens, long K, narrow C_o) without workspace
+    need = L.sq_workspace_bytes(sq.OP_W8A8_LINEAR, 16, 12288, 1536)
     assert need > 0
-    assert L.sq_w8a8_linear(fake, fake, 1, fake, fake, NULL, NULL, 0, fake, 0, 16, 12288, 12288, 0, NULL, 0, NULL) == 5
+    assert L.sq_w8a8_linear(fake, fake, 1, fake, fake, NULL, NULL, 0, fake, 0, 16, 12288, 1536, 0, NULL, 0, NULL) == 5
+    # few tokens against a wide C_o stream W in one pass: no workspace
+    assert L.sq_workspace_bytes(sq.OP_W8A8_LINEAR, 16, 12288, 12288) == 0
     assert L.sq_i8_gemm_i32(fake, NULL, fake, 4, 64, 64, 0, NULL, 0, NULL) == 1
     # bmm
     assert L.sq_w8a8_bmm(fake, fake, 1, 1.0, fake, 0, 0, 16, 16, 16, 256, 256, 256, NULL) == 2
