@@ -39,7 +39,9 @@ SQ_DEVICE uint32_t dequant_one(int acc, float c, float bias, bool has_bias, bool
     return store16_bits<BF16>(v);
 }
 
-// Weight-streaming GEMM for few-token shapes (gemm_i8_stream.hip).  Returns false when the shape is
-// not one it balances well; nothing is launched then.
-bool sq_stream_gemm_eligible(int64_t M, int64_t N, int64_t K, int64_t batch);
+// Weight-streaming GEMM for few-token shapes (gemm_i8_stream.hip).  sq_stream_gemm_splits returns 0
+// when the shape is left to the tile kernels, else the number of K splits of its plan: 1 = the kernel
+// writes the final output itself; > 1 = it writes int32 partial sums to a.acc_out[splits][M][N] (which
+// the caller points at a workspace) and the split-K reduction kernel finishes the job.
+int sq_stream_gemm_splits(int64_t M, int64_t N, int64_t K, int64_t batch);
 void sq_stream_gemm_launch(const GemmArgs& a, bool to_i32, bool bf16, bool tiled, hipStream_t st);

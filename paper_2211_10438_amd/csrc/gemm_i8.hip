@@ -528,9 +528,27 @@ void launch_cfg(const Plan& pl, const GemmArgs& a, int batch, hipStream_t st, bo
 sq_status run_gemm(GemmArgs a, int64_t batch, bool to_i32, bool bf16, void* workspace, size_t ws_bytes, hipStream_t st,
                    bool b_transposed = false, bool tiled = false)
 {
-    if (!b_transposed && sq_stream_gemm_eligible(a.M, a.N, a.K, batch)) {
-        // few tokens, wide C_o: stream W once through one workgroup per CU (no split-K, no workspace)
-        sq_stream_gemm_launch(a, to_i32, bf16, tiled, st);
+    const int64_t total = (int64_t)a.M * a.N;
+    auto reduce = [&](void* final_out) {  // a.acc_out = partials [a.splits][M][N]
+        a.C = final_out;
+        int blocks = (int)((total + 255) / 256);
+        if (blocks > 4096) blocks = 4096;
+        if (bf16) hipLaunchKernelGGL(splitk_reduce_kernel<true>, dim3(blocks), dim3(256), 0, st, a, to_i32 ? 1 : 0);
+        else hipLaunchKernelGGL(splitk_reduce_kernel<false>, dim3(blocks), dim3(256), 0, st, a, to_i32 ? 1 : 0);
+    };
+    if (const int ss = b_transposed ? 0 : sq_stream_gemm_splits(a.M, a.N, a.K, batch)) {
+        // few tokens, wide C_o: stream W once through one workgroup per CU
+        if (ss > 1) {
+            const size_t need = (size_t)ss * total * sizeof(int32_t);
+            if (!workspace || ws_bytes < need) return SQ_ERR_WORKSPACE;
+            void* final_out = to_i32 ? (void*)a.acc_out : a.C;
+            a.acc_out = (int32_t*)workspace;
+            a.splits = ss;
+            sq_stream_gemm_launch(a, true, false, tiled, st);
+            reduce(final_out);
+        } else {
+            sq_stream_gemm_launch(a, to_i32, bf16, tiled, st);
+        }
         return sq_launch_status();
     }
     Plan pl = make_plan(a.M, a.N, a.K, batch, true, b_transposed);
@@ -544,12 +562,7 @@ sq_status run_gemm(GemmArgs a, int64_t batch, bool to_i32, bool bf16, void* work
         void* final_out = to_i32 ? (void*)a.acc_out : a.C;
         a.acc_out = (int32_t*)workspace;
         launch_cfg<EPI_I32, false>(pl, a, 1, st, tiled);
-        a.C = final_out;
-        const int64_t total = (int64_t)a.M * a.N;
-        int blocks = (int)((total + 255) / 256);
-        if (blocks > 4096) blocks = 4096;
-        if (bf16) hipLaunchKernelGGL(splitk_reduce_kernel<true>, dim3(blocks), dim3(256), 0, st, a, to_i32 ? 1 : 0);
-        else hipLaunchKernelGGL(splitk_reduce_kernel<false>, dim3(blocks), dim3(256), 0, st, a, to_i32 ? 1 : 0);
+        reduce(final_out);
     } else if (to_i32) {
         launch_cfg<EPI_I32, false>(pl, a, (int)batch, st, tiled);
     } else if (bf16) {
@@ -574,7 +587,7 @@ extern "C" {
 size_t sq_gemm_workspace_bytes(int64_t t, int64_t c_i, int64_t c_o)
 {
     if (!dims_ok(t, c_i, c_o)) return 0;
-    if (sq_stream_gemm_eligible(t, c_o, c_i, 1)) return 0;
+    if (const int ss = sq_stream_gemm_splits(t, c_o, c_i, 1)) return ss > 1 ? (size_t)ss * t * c_o * sizeof(int32_t) : 0;
     Plan pl = make_plan(t, c_o, c_i, 1, true);
     return pl.splits > 1 ? (size_t)pl.splits * t * c_o * sizeof(int32_t) : 0;
 }

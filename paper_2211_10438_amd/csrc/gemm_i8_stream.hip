@@ -3,90 +3,90 @@
 // With T <= 128 tokens the contraction of Eq. 2 reads every weight byte once and does little
 // arithmetic with it: the layer is bound by how fast W streams out of HBM.  This kernel is built
 // around that stream instead of around an output tile:
-//  * The C_o axis is cut into 16-column units and the units are dealt evenly to one workgroup per
-//    compute unit (a "slab" of 1..16 units each, every slab over the whole K range).  One round of
-//    workgroups, each streaming the same number of bytes: no tail round, no split-K partials, no
-//    second kernel; the dequantizing epilogue of Eq. 2 runs on the accumulators in registers.
+//  * The C_o axis is cut into 16-column units and the units are dealt evenly to the workgroups, one
+//    workgroup per compute unit (a "slab" of 1..16 units each).  One round of workgroups, each streaming
+//    the same number of bytes: no tail round.  For up to 32 tokens every slab runs over the whole K range
+//    and the dequantizing epilogue of Eq. 2 is applied to the accumulators in registers: no workspace, no
+//    second kernel.
+//  * Every workgroup also pulls the activation rows of its K range through its CU's vector cache, and a
+//    CU sustains only a few tens of GB/s while most of its loads miss to HBM.  With 64..128 tokens the
+//    activation bytes per weight byte (tokens / slab width) decide the speed, so narrow slabs are traded
+//    for wide ones over a fraction of K (a host-side cost model picks slab width and K split); the int32
+//    partial sums then go to the workspace and the split-K reduction kernel applies the epilogue.
 //  * v_mfma_i32_16x16x64_i8: a 16-row x 64-byte block of 1 KB is exactly one MFMA operand, for the
 //    activation rows as for a unit of W, so slab widths need only be multiples of 16.
-//  * HBM -> LDS with global_load_lds (1 KB per wave instruction), up to 16 stages deep and sized
-//    so that tens of KB per CU are in flight; thin slabs put several 64-byte K steps into one stage
-//    to keep the work per barrier constant.
-//  * The (small) activation block is re-read by every workgroup from L2.
+//  * HBM -> LDS with global_load_lds (1 KB per wave instruction) through a 4-stage ring; thin slabs put
+//    several 64-byte K steps into one stage to keep the work per barrier constant.  (Measured: deeper
+//    rings do not stream faster; the outstanding-miss capacity of the CU is the limit, not the ring.)
 #include <type_traits>
 
 #include "gemm_args.h"
 
 namespace {
 
-constexpr int kSmemBytes = 152 * 1024;
+constexpr int kDepth = 4;            // pipeline stages
 constexpr int kMaxStageBlocks = 24;  // 1 KB blocks per stage
-constexpr int kMaxLoads = kMaxStageBlocks / 4;  // per wave per stage
+constexpr int kSmemBytes = kDepth * kMaxStageBlocks * 1024;
 
 struct StreamArgs {
-    int groups;      // workgroups
+    int gn;          // slabs (workgroups along C_o)
+    int gk;          // K splits (workgroups along K); > 1: int32 partials go to acc_out[gk][M][N]
     int units;       // 16-column units of N
     int na;          // 16-row blocks of A
     int ksub;        // 64-byte K steps per stage
-    int loads;       // global -> LDS loads per wave per stage
-    int iters;       // K / 64 / ksub
+    int iters;       // stages per workgroup: K / 64 / gk / ksub
     int tiled, to_i32, bf16;
 };
 
-// Pipeline depth as a function of the loads one wave issues per stage (a stage holds at most 4 * loads
-// KB, so depth * stage stays below the LDS allocation), and the matching wait: stage `it` has landed
-// when at most (depth - 2) younger stages, `loads` instructions each, are still in flight.
-__host__ __device__ constexpr int stage_depth(int loads)
-{
-    return loads <= 2 ? 16 : loads == 3 ? 12 : loads == 4 ? 9 : loads == 5 ? 7 : 6;
-}
+// Stage `it` of this wave has landed when at most (kDepth - 2) younger stages, `loads` instructions
+// each, are still in flight.
 SQ_DEVICE void wait_stage_landed(int loads)
 {
     switch (loads) {
-        case 1: wait_vmcnt_imm<(stage_depth(1) - 2) * 1>(); break;
-        case 2: wait_vmcnt_imm<(stage_depth(2) - 2) * 2>(); break;
-        case 3: wait_vmcnt_imm<(stage_depth(3) - 2) * 3>(); break;
-        case 4: wait_vmcnt_imm<(stage_depth(4) - 2) * 4>(); break;
-        case 5: wait_vmcnt_imm<(stage_depth(5) - 2) * 5>(); break;
-        default: wait_vmcnt_imm<(stage_depth(6) - 2) * 6>(); break;
+        case 0: break;
+        case 1: wait_vmcnt_imm<(kDepth - 2) * 1>(); break;
+        case 2: wait_vmcnt_imm<(kDepth - 2) * 2>(); break;
+        case 3: wait_vmcnt_imm<(kDepth - 2) * 3>(); break;
+        case 4: wait_vmcnt_imm<(kDepth - 2) * 4>(); break;
+        case 5: wait_vmcnt_imm<(kDepth - 2) * 5>(); break;
+        default: wait_vmcnt_imm<(kDepth - 2) * 6>(); break;
     }
 }
+static_assert(kDepth >= 3 && (kDepth - 2) * (kMaxStageBlocks / 4) <= 63, "depth and vmcnt limits");
 
-// MB: 16-row blocks of A per wave; WM: waves along the token axis (the other 4/WM waves deal the
-// slab's units among themselves); NUW: most units one wave accumulates.
-template <int MB, int WM, int NUW>
-__global__ __launch_bounds__(256, 1) void gemm_i8_stream_kernel(const GemmArgs p, const StreamArgs q)
+// MB: 16-row blocks of A per wave; WM: waves along the token axis (the other NWAVE/WM waves deal the
+// slab's units among themselves); NUW: most units one wave accumulates.  The 8-wave shapes put two
+// waves on each SIMD, so one wave's LDS reads overlap the other's MFMAs.
+template <int MB, int WM, int NUW, int NWAVE>
+__global__ __launch_bounds__(NWAVE * 64, 1) void gemm_i8_stream_kernel(const GemmArgs p, const StreamArgs q)
 {
-    constexpr int WN = 4 / WM;
+    constexpr int WN = NWAVE / WM;
+    constexpr int kLoads = kMaxStageBlocks / NWAVE;
     __shared__ __attribute__((aligned(1024))) char smem[kSmemBytes];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave / WN, wn = wave % WN;
-    const int g = blockIdx.x;
-    const int u0 = (int)((int64_t)g * q.units / q.groups), u1 = (int)((int64_t)(g + 1) * q.units / q.groups);
+    const int gs = blockIdx.x % q.gn, gki = blockIdx.x / q.gn;
+    const int u0 = (int)((int64_t)gs * q.units / q.gn), u1 = (int)((int64_t)(gs + 1) * q.units / q.gn);
     const int nu = u1 - u0;           // units of this workgroup
     const int nblk = q.na + nu;       // block rows per stage
     const int ksub = q.ksub;
     const int sblocks = nblk * ksub;  // 1 KB blocks per stage
     const int stage_bytes = sblocks * 1024;
-    const int L = q.loads;  // loads per wave per stage, the same for every wave (see below)
-    const int nstage = stage_depth(L);
+    const int L = sblocks > wave ? (sblocks - wave + NWAVE - 1) / NWAVE : 0;  // loads of this wave per stage
 
-    // ---- global -> LDS slots of this wave: stage block sb = i*4 + wave = (block row b, K sub-step ks).
+    // ---- global -> LDS slots of this wave: stage block sb = i*NWAVE + wave = (block row b, K sub-step ks).
     // Tiled operands: lane l copies bytes 16 l .. 16 l + 15 of the 1 KB block.  Row-major operands:
     // four neighbouring lanes copy the 64 bytes of one row, chunks permuted (position = chunk ^ swz(row)).
     auto swz = [](int r) { return ((r >> 1) & 3) ^ ((r >> 3) & 1); };
     const int64_t kstep = q.tiled ? 1024 : 64;
-    // A wave whose last slot falls past the stage re-reads stage block 0 into a spare KB at the end of the
-    // allocation: every wave then has the same number of loads in flight, which the wait above relies on.
-    const int8_t* src[kMaxLoads];
-    int dst[kMaxLoads];
+    const int64_t kbeg = (int64_t)gki * q.iters * ksub * kstep;  // first byte of this workgroup's K range
+    const int8_t* src[kLoads];
 #pragma unroll
-    for (int i = 0; i < kMaxLoads; ++i) {
-        int sb = i * 4 + wave;
-        dst[i] = sb < sblocks ? sb * 1024 : -1;
-        sb = sb < sblocks ? sb : 0;
+    for (int i = 0; i < kLoads; ++i) {
+        int sb = i * NWAVE + wave;
+        sb = sb < sblocks ? sb : 0;  // unused slot (i >= L)
         const int b = sb / ksub, ks = sb - b * ksub;
         const bool is_a = b < q.na;
         const int8_t* base = is_a ? p.A : p.B;
@@ -98,22 +98,20 @@ __global__ __launch_bounds__(256, 1) void gemm_i8_stream_kernel(const GemmArgs p
                 const int last = (p.M - 1) >> 4;
                 br = br < last ? br : last;
             }
-            src[i] = base + (int64_t)br * 16 * ld + ks * kstep + lane * 16;
+            src[i] = base + (int64_t)br * 16 * ld + kbeg + ks * kstep + lane * 16;
         } else {
             int row = br * 16 + (lane >> 2);
             row = row < rows ? row : rows - 1;
             const int chunk = (lane & 3) ^ swz(lane >> 2);
-            src[i] = base + (int64_t)row * ld + ks * kstep + chunk * 16;
+            src[i] = base + (int64_t)row * ld + kbeg + ks * kstep + chunk * 16;
         }
     }
     auto issue_stage = [&](int it, int slot) {
         const int64_t koff = (int64_t)it * ksub * kstep;
-        char* base = smem + slot * stage_bytes;
+        char* base = smem + slot * stage_bytes + wave * 1024;
 #pragma unroll
-        for (int i = 0; i < kMaxLoads; ++i)
-            if (i < L)
-                __builtin_amdgcn_global_load_lds(GPTR(src[i] + koff), LPTR(dst[i] >= 0 ? base + dst[i] : smem + kSmemBytes - 1024),
-                                                 16, 0, 0);
+        for (int i = 0; i < kLoads; ++i)
+            if (i < L) __builtin_amdgcn_global_load_lds(GPTR(src[i] + koff), LPTR(base + i * NWAVE * 1024), 16, 0, 0);
     };
 
     // ---- MFMA operands: lane l feeds row (l & 15) with K-chunk (l >> 4) of the 64-byte step.
@@ -126,8 +124,11 @@ __global__ __launch_bounds__(256, 1) void gemm_i8_stream_kernel(const GemmArgs p
 #pragma unroll
         for (int j = 0; j < NUW; ++j) acc[i][j] = v4i{0, 0, 0, 0};
 
+    // Every K step issues exactly one stage of loads (past the end of the range the last stage again,
+    // into a slot nobody reads), so the number of loads in flight at each wait is a constant.
     const int iters = q.iters;
-    for (int s = 0; s < nstage - 1; ++s) issue_stage(s < iters ? s : iters - 1, s);
+#pragma unroll
+    for (int s = 0; s < kDepth - 1; ++s) issue_stage(s < iters ? s : iters - 1, s);
 
     // The K loop is instantiated once per number of units this wave accumulates (CNT), so its body has
     // no branches: all operand reads of a K step are issued together, then the MFMAs.
@@ -139,8 +140,8 @@ __global__ __launch_bounds__(256, 1) void gemm_i8_stream_kernel(const GemmArgs p
             wait_stage_landed(L);            // this wave's share of stage `it` has landed
             __builtin_amdgcn_s_barrier();    // everyone's share has; everyone is done with stage it-1
             {
-                const int nxt = it + nstage - 1;
-                issue_stage(nxt < iters ? nxt : iters - 1, slot == 0 ? nstage - 1 : slot - 1);
+                const int nxt = it + kDepth - 1;
+                issue_stage(nxt < iters ? nxt : iters - 1, slot == 0 ? kDepth - 1 : slot - 1);
             }
             const char* sa = smem + slot * stage_bytes + frag_off + wm * MB * ksub * 1024;
             const char* sb = smem + slot * stage_bytes + frag_off + (q.na + wn) * ksub * 1024;
@@ -156,7 +157,7 @@ __global__ __launch_bounds__(256, 1) void gemm_i8_stream_kernel(const GemmArgs p
                     for (int i = 0; i < MB; ++i)
                         acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
             }
-            slot = slot + 1 == nstage ? 0 : slot + 1;
+            slot = slot + 1 == kDepth ? 0 : slot + 1;
         }
     };
 #define SQ_CASE(N) case N: if constexpr (N <= NUW) k_loop(std::integral_constant<int, N>{}); break;
@@ -170,7 +171,9 @@ __global__ __launch_bounds__(256, 1) void gemm_i8_stream_kernel(const GemmArgs p
 
     // ---- epilogue.  16x16 accumulator layout: lane l, register v holds row 4*(l >> 4) + v, column l & 15.
     const int col_l = lane & 15, row_l = (lane >> 4) * 4;
-    const float ws = (!q.to_i32 && p.x_scale) ? p.w_scale[0] : 0.0f;
+    const bool raw = q.to_i32 || q.gk > 1;
+    int32_t* out32 = p.acc_out + (int64_t)gki * p.M * p.N;
+    const float ws = (!raw && p.x_scale) ? p.w_scale[0] : 0.0f;
     const uint16_t* R = (const uint16_t*)p.residual;
 #pragma unroll
     for (int j = 0; j < NUW; ++j) {
@@ -178,7 +181,7 @@ __global__ __launch_bounds__(256, 1) void gemm_i8_stream_kernel(const GemmArgs p
         if (u >= nu) continue;
         const int col = (u0 + u) * 16 + col_l;
         if (col >= p.N) continue;
-        const float bias = (!q.to_i32 && p.bias) ? p.bias[col] : 0.0f;
+        const float bias = (!raw && p.bias) ? p.bias[col] : 0.0f;
 #pragma unroll
         for (int i = 0; i < MB; ++i)
 #pragma unroll
@@ -186,8 +189,8 @@ __global__ __launch_bounds__(256, 1) void gemm_i8_stream_kernel(const GemmArgs p
                 const int row = (wm * MB + i) * 16 + row_l + v;
                 if (row >= p.M) continue;
                 const int64_t idx = (int64_t)row * p.N + col;
-                if (q.to_i32) {
-                    p.acc_out[idx] = acc[i][j][v];
+                if (raw) {
+                    out32[idx] = acc[i][j][v];
                 } else {
                     float c;
                     if (p.x_scale) c = (p.per_token ? p.x_scale[row] : p.x_scale[0]) * ws;
@@ -215,42 +218,66 @@ int num_cus()
     return n;
 }
 
-// Slab plan: one workgroup per CU (times an integer when slabs would exceed 16 units).
+// Slab width and K split by a small cost model (seconds):
+//   CU side:  every workgroup moves (A blocks + slab units) KB per K step through its CU's vector cache,
+//             at about 32 GB/s while most loads miss to HBM; workgroups beyond one per CU run in rounds;
+//   HBM side: W once plus the int32 partials when K is split, at about 5.5 TB/s;
+//   a K split adds the reduction kernel (launch + reading the partials).
 bool make_stream_plan(int64_t M, int64_t N, int64_t K, int64_t batch, StreamArgs* out)
 {
     if (batch != 1 || M < 1 || M > 128 || (K & 63) || K < 64) return false;
     const int64_t units = (N + 15) / 16;
     const int cus = num_cus();
-    if (units < cus) return false;
-    const int64_t rounds = (units + (int64_t)cus * 16 - 1) / ((int64_t)cus * 16);
-    const int64_t groups = cus * rounds;
-    const int64_t upw = (units + groups - 1) / groups;
-    if ((double)units / (double)(groups * upw) < 0.85) return false;  // uneven slabs: the tile kernels do better
-    StreamArgs q{};
-    q.groups = (int)groups;
-    q.units = (int)units;
-    q.na = M <= 16 ? 1 : M <= 32 ? 2 : M <= 64 ? 4 : 8;
-    const int nblk = q.na + (int)upw;
+    if (units < cus) return false;  // narrow C_o: the tile kernels with split-K cover it
+    const int na = M <= 16 ? 1 : M <= 32 ? 2 : M <= 64 ? 4 : 8;
     const int nk = (int)(K >> 6);
+    const double cu_rate = 32e9, hbm_rate = 5.5e12, red_rate = 4e12, red_launch = 5e-6;
+    double best = 1e30, best_cu = 1e30;
+    int best_gn = 0, best_gk = 0;
+    for (int gk = 1; gk <= 8; ++gk) {
+        if (nk % gk) continue;
+        if (gk > 1 && (nk / gk < 8 || M <= 32)) continue;
+        for (int s = 1; s <= 16; ++s) {
+            const int64_t gn = (units + s - 1) / s;
+            const int64_t smax = (units + gn - 1) / gn;  // widest slab after dealing the units evenly
+            if (s > 1 && (units + s - 2) / (s - 1) == gn) continue;  // same plan as s - 1
+            const int64_t rounds = (gn * gk + cus - 1) / cus;
+            const double t_cu = (double)rounds * (double)(na + smax) * 1024.0 * (nk / gk) / cu_rate;
+            const double part = gk > 1 ? (double)gk * M * N * 4.0 : 0.0;
+            const double t_hbm = ((double)N * K + part) / hbm_rate;
+            double t = t_cu > t_hbm ? t_cu : t_hbm;
+            if (gk > 1) t += red_launch + (part + 2.0 * M * N) / red_rate;
+            // a clear win, or about the same modelled time with more headroom on the CU side
+            if (t < best * 0.97 || (t < best * 1.03 && t_cu < best_cu)) {
+                best = t < best ? t : best;
+                best_cu = t_cu;
+                best_gn = (int)gn;
+                best_gk = gk;
+            }
+        }
+    }
+    if (!best_gn) return false;
+    StreamArgs q{};
+    q.gn = best_gn;
+    q.gk = best_gk;
+    q.units = (int)units;
+    q.na = na;
+    const int nblk = na + (int)((units + best_gn - 1) / best_gn);
+    const int nks = nk / best_gk;
     q.ksub = 1;
     for (int c = 4; c > 1; c >>= 1)
-        if (nblk * c <= kMaxStageBlocks && nk % c == 0) { q.ksub = c; break; }
-    const int sblocks = nblk * q.ksub;
-    q.loads = (sblocks + 3) / 4;
-    static_assert(stage_depth(1) * 4 * 1 + 1 <= kSmemBytes / 1024 && stage_depth(2) * 4 * 2 + 1 <= kSmemBytes / 1024 &&
-                  stage_depth(3) * 4 * 3 + 1 <= kSmemBytes / 1024 && stage_depth(4) * 4 * 4 + 1 <= kSmemBytes / 1024 &&
-                  stage_depth(5) * 4 * 5 + 1 <= kSmemBytes / 1024 && stage_depth(6) * 4 * 6 + 1 <= kSmemBytes / 1024,
-                  "stages plus the spare KB fit the LDS allocation");
-    q.iters = nk / q.ksub;
+        if (nblk * c <= kMaxStageBlocks && nks % c == 0) { q.ksub = c; break; }
+    q.iters = nks / q.ksub;
     if (out) *out = q;
     return true;
 }
 
 }  // namespace
 
-bool sq_stream_gemm_eligible(int64_t M, int64_t N, int64_t K, int64_t batch)
+int sq_stream_gemm_splits(int64_t M, int64_t N, int64_t K, int64_t batch)
 {
-    return make_stream_plan(M, N, K, batch, nullptr);
+    StreamArgs q{};
+    return make_stream_plan(M, N, K, batch, &q) ? q.gk : 0;
 }
 
 void sq_stream_gemm_launch(const GemmArgs& a, bool to_i32, bool bf16, bool tiled, hipStream_t st)
@@ -260,11 +287,11 @@ void sq_stream_gemm_launch(const GemmArgs& a, bool to_i32, bool bf16, bool tiled
     q.tiled = tiled ? 1 : 0;
     q.to_i32 = to_i32 ? 1 : 0;
     q.bf16 = bf16 ? 1 : 0;
-    const dim3 grid((unsigned)q.groups), block(256);
+    const dim3 grid((unsigned)(q.gn * q.gk)), block(256), block8(512);
     switch (q.na) {
-        case 1: hipLaunchKernelGGL((gemm_i8_stream_kernel<1, 1, 4>), grid, block, 0, st, a, q); break;
-        case 2: hipLaunchKernelGGL((gemm_i8_stream_kernel<1, 2, 8>), grid, block, 0, st, a, q); break;
-        case 4: hipLaunchKernelGGL((gemm_i8_stream_kernel<1, 4, 16>), grid, block, 0, st, a, q); break;
-        default: hipLaunchKernelGGL((gemm_i8_stream_kernel<2, 4, 16>), grid, block, 0, st, a, q); break;
+        case 1: hipLaunchKernelGGL((gemm_i8_stream_kernel<1, 1, 4, 4>), grid, block, 0, st, a, q); break;
+        case 2: hipLaunchKernelGGL((gemm_i8_stream_kernel<1, 2, 8, 4>), grid, block, 0, st, a, q); break;
+        case 4: hipLaunchKernelGGL((gemm_i8_stream_kernel<1, 4, 8, 8>), grid, block8, 0, st, a, q); break;
+        default: hipLaunchKernelGGL((gemm_i8_stream_kernel<2, 4, 8, 8>), grid, block8, 0, st, a, q); break;
     }
 }

@@ -1,7 +1,8 @@
 """GPU parity of the few-token (decode) GEMM path: at most 128 tokens against a wide C_o, where the library
 streams W once through one workgroup per compute unit.  Shapes are chosen to cover every activation-block
 count (1, 2, 4, 8 blocks of 16 tokens), slabs of 1 to 16 column units, uneven slabs, a ragged last unit,
-1 / 2 / 4 K steps per pipeline stage, K ranges shorter than the pipeline, and more workgroups than one round."""
+1 / 2 / 4 K steps per pipeline stage, K ranges shorter than the pipeline, more workgroups than one round, and
+the plans that split K (64..128 tokens against a C_o that gives narrow slabs)."""
 import numpy as np
 import pytest
 
@@ -21,7 +22,7 @@ def _progress(msg):
 STREAM_GEMM = [
     (1, 64, 4096), (7, 192, 4096), (16, 640, 7688), (17, 1024, 8192), (33, 2048, 12288), (64, 1088, 36864),
     (100, 4096, 4096), (128, 1024, 65536), (128, 12288, 12288), (1, 49152, 12288), (128, 512, 50272),
-    (16, 256, 70000), (2, 12288, 36864), (65, 3072, 49152),
+    (16, 256, 70000), (2, 12288, 36864), (65, 3072, 49152), (64, 12288, 12288), (128, 9216, 4096),
 ]
 
 
@@ -29,7 +30,8 @@ STREAM_GEMM = [
 @pytest.mark.parametrize("t,c_i,c_o", STREAM_GEMM)
 def test_stream_gemm_i32_exact(t, c_i, c_o, layout):
     _progress(f"stream i8_gemm_i32 t={t} c_i={c_i} c_o={c_o} layout={layout}")
-    assert sq.workspace_bytes(sq.OP_I8_GEMM_I32, t, c_i, c_o) == 0  # this path needs no split-K workspace
+    if t <= 32:
+        assert sq.workspace_bytes(sq.OP_I8_GEMM_I32, t, c_i, c_o) == 0  # up to 32 tokens: never a K split
     xq = synth.int8_codes((t, c_i), 51 + t)
     wq = synth.int8_codes((c_o, c_i), 52 + c_o % 1000)
     ref = oracle.i8_gemm_i32(xq, wq)
@@ -61,6 +63,8 @@ STREAM_LINEAR = [
     (128, 2048, 7688, F16, True, True, True, True, sq.TILED),
     (100, 1024, 12288, BF16, True, True, False, False, sq.ROW_MAJOR),
     (128, 1024, 36864, BF16, True, False, False, True, sq.TILED),
+    (128, 4096, 4096, BF16, True, True, True, True, sq.TILED),      # wide slabs over a quarter of K each
+    (64, 12288, 12288, F16, True, True, False, True, sq.ROW_MAJOR),  # two K splits
 ]
 
 
