@@ -164,6 +164,38 @@ def main():
     gemm_tops = total_ops / (gemm_ms * 1e-3) / 1e12
     quant_bytes = sum(3.0 * L["t"] * L["c_i"] + 4.0 * L["t"] for L in layers)
 
+    # Decode shapes (Sec. 5.3's generation stage): the same four layers at 1 / 16 / 128 tokens.  Every pass streams
+    # all 1.8 GB of int8 weights, far more than any cache holds, so each layer's W comes from HBM every time.
+    decode = {}
+    for m in (1, 16, 128):
+        bufs = []
+        for L in layers:
+            xs_in = L["x"][:m].contiguous()
+            nws = sq.workspace_bytes(sq.OP_W8A8_LINEAR, m, L["c_i"], L["c_o"])
+            bufs.append(dict(x=xs_in, xq=sq.empty_codes(m, L["c_i"], sq.TILED),
+                             xs=torch.empty(m, dtype=torch.float32, device="cuda"),
+                             y=torch.empty((m, L["c_o"]), dtype=torch.bfloat16, device="cuda"),
+                             ws=torch.empty(max(nws, 16), dtype=torch.uint8, device="cuda")))
+
+        def dstep():
+            for L, b in zip(layers, bufs):
+                sq.quantize_act(b["x"], sq.PER_TOKEN_DYNAMIC, inv_s=L["inv_s"], out=(b["xq"], b["xs"]), layout=sq.TILED)
+                sq.w8a8_linear(b["xq"], b["xs"], L["wq"], L["w_scale"], torch.bfloat16, out=b["y"], workspace=b["ws"],
+                               layout=sq.TILED)
+        for _ in range(args.warmup):
+            dstep()
+        d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        d0.record()
+        for _ in range(args.steps):
+            dstep()
+        d1.record()
+        torch.cuda.synchronize()
+        dms = d0.elapsed_time(d1) / args.steps
+        dbytes = sum(L["c_i"] * L["c_o"] + 4.0 * m * L["c_i"] + 2.0 * m * L["c_o"] for L in layers)
+        decode[f"M{m}"] = {"ms_per_step": round(dms, 4), "achieved_GBs": round(dbytes / dms / 1e6, 1),
+                           "frac_hbm_peak": round(dbytes / dms / 1e6 / PEAK_HBM_GBS, 4),
+                           "tops": round(sum(2.0 * m * L["c_i"] * L["c_o"] for L in layers) / dms / 1e9, 2)}
+
     # HBM-side traffic of the GEMM launches: measured separately with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on
     # `bench.py --probe` (counters cannot be read from inside this process); the summary is kept under profiles/.
     traffic = None
@@ -199,6 +231,9 @@ def main():
         "quantize_pass": {"bound": "hbm", "achieved_GBs": round(quant_bytes / (quant_ms * 1e-3) / 1e9, 1),
                           "peak_GBs": PEAK_HBM_GBS, "frac": round(quant_bytes / (quant_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
     }
+    out["decode"] = {"bound": "hbm", "peak_GBs": PEAK_HBM_GBS,
+                     "note": "same four layers, quantize + linear per layer, bytes = int8 W + fp16 x in + codes out/in + "
+                             "bf16 y out; weights stream from HBM on every pass (1.8 GB per pass)", **decode}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(desc)
     print(json.dumps(out))
