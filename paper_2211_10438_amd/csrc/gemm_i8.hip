@@ -43,8 +43,13 @@ enum { EPI_DEQUANT = 0, EPI_I32 = 1 };
 //             serves best.
 enum { LAY_ROWS = 0, LAY_BT = 1, LAY_TILED = 2 };
 
-template <int BM, int BN, int WGM, int WGN, int NSTAGE, int EPI, bool BF16, int LAY>
-__global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArgs p)
+//
+// ONESHOT (host guarantees K <= 64 * (NSTAGE - 1)): the whole K range is fetched up front into NSTAGE - 1
+// buffers, no refills, no barriers in the K loop.  Used for attention scores (K = head_dim), where the
+// kernel is bound by writing its output and several small workgroups per CU (OCC) overlap each other's
+// load, MFMA and store phases.
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, int EPI, bool BF16, int LAY, int OCC = 1, bool ONESHOT = false>
+__global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmArgs p)
 {
     constexpr bool BT = LAY == LAY_BT, TILED = LAY == LAY_TILED;
     constexpr int NW = WGM * WGN, BK = 64;
@@ -59,7 +64,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
     static_assert(NSTAGE >= 3 && (NSTAGE - 2) * LPS <= 63, "pipeline depth exceeds the 6-bit vmcnt");
     static_assert(NSTAGE * STAGE <= 160 * 1024, "LDS budget");
     constexpr int EPI_BYTES = EPI == EPI_DEQUANT ? BM * (BN * 2 + 16) : 0;
-    constexpr int SMEM_BYTES = NSTAGE * STAGE > EPI_BYTES ? NSTAGE * STAGE : EPI_BYTES;
+    constexpr int RING_BYTES = (ONESHOT ? NSTAGE - 1 : NSTAGE) * STAGE;
+    constexpr int SMEM_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
+    static_assert(!ONESHOT || !BT, "one-shot loading is not combined with the transposed-B path");
     static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
     __shared__ __attribute__((aligned(1024))) char smem[SMEM_BYTES];
 
@@ -233,8 +240,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
         for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int j = 0; j < NI; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j], fa[i], acc[i][j], 0, 0, 0);
     };
+    // (B rows feed the MFMA's first operand: each accumulator block is the transpose of its 32x32 output
+    // block, so a lane ends up with runs of four neighbouring output columns of one row -- see the epilogue.)
     // Scheduling hint for one half step (MI+NI fragment reads of the next half, MI*NI MFMAs of this
     // one): interleave the LDS reads with the MFMAs so the four waves of the workgroup do not hit
     // the LDS pipe in one burst.
@@ -259,8 +268,16 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
     // constant (one immediate s_waitcnt value) and the loop body free of branches, so the loads and
     // LDS reads can be interleaved with the MFMAs by the scheduler hints below.
 #pragma unroll
-    for (int s = 0; s < NSTAGE - 1; ++s) issue_stage(s < nk ? s : nk - 1, s);
-    if constexpr (BT) {
+    for (int s = 0; s < NSTAGE - 1; ++s) {
+        if constexpr (ONESHOT) {
+            if (s < nk) issue_stage(s, s);
+        } else {
+            issue_stage(s < nk ? s : nk - 1, s);
+        }
+    }
+    if constexpr (ONESHOT) {
+        wait_vmcnt_imm<0>();
+    } else if constexpr (BT) {
         // B stages 0 and 1 go through registers synchronously (which also drains the DMA loads above);
         // stage 2 stays in registers and is written to LDS during K step 0.
         load_b(0);
@@ -284,16 +301,18 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
         interleave_hint(std::integral_constant<int, 0>{});
         // second half; meanwhile make stage it+1 visible and refill the buffer freed by step it-1
         const int nbuf = buf + 1 == NSTAGE ? 0 : buf + 1;
-        wait_vmcnt_imm<(NSTAGE - 3) * LPS>();
-        __builtin_amdgcn_s_barrier();
-        if constexpr (BT) {
-            store_b(buf + 2 >= NSTAGE ? buf + 2 - NSTAGE : buf + 2);
-            load_b(it + 3 < nk ? it + 3 : nk - 1);
+        if constexpr (!ONESHOT) {
+            wait_vmcnt_imm<(NSTAGE - 3) * LPS>();
+            __builtin_amdgcn_s_barrier();
+            if constexpr (BT) {
+                store_b(buf + 2 >= NSTAGE ? buf + 2 - NSTAGE : buf + 2);
+                load_b(it + 3 < nk ? it + 3 : nk - 1);
+            }
+            issue_stage(it + NSTAGE - 1 < nk ? it + NSTAGE - 1 : nk - 1, buf == 0 ? NSTAGE - 1 : buf - 1);
         }
-        issue_stage(it + NSTAGE - 1 < nk ? it + NSTAGE - 1 : nk - 1, buf == 0 ? NSTAGE - 1 : buf - 1);
         read_frags(fa0, fb0, nbuf, 0);
         mfma_all(fa1, fb1);
-        interleave_hint(std::integral_constant<int, BT ? 0 : SA + SB>{});
+        interleave_hint(std::integral_constant<int, (BT || ONESHOT) ? 0 : SA + SB>{});
         buf = nbuf;
     }
     // last K step
@@ -311,24 +330,33 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
     mfma_all(fa1, fb1);
     wait_vmcnt_imm<0>();  // the refills issued past the end of the K range have landed
 
-    // ---- epilogue.  32x32 accumulator layout: lane l, register v holds
-    // row 8*(v/4) + 4*(l>>5) + (v&3), column (l & 31).
-    const int col_l = lane & 31, row_l = (lane >> 5) * 4;
+    // ---- epilogue.  Accumulator block (i, j) is the transposed 32x32 output block: lane l, register v
+    // holds output row (l & 31), column 8*(v/4) + 4*(l >> 5) + (v & 3) of the block, i.e. registers
+    // 4g .. 4g+3 are four neighbouring columns of one row.
+    const int row_l = lane & 31, col_l = (lane >> 5) * 4;
     if constexpr (EPI == EPI_I32) {
         int32_t* out = p.acc_out + ((int64_t)split * p.M) * p.N;
+        const bool vec4 = (p.N & 3) == 0;  // 16-byte stores stay aligned and inside the row
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+        for (int i = 0; i < MI; ++i) {
+            const int row = m0 + wm * WM + i * 32 + row_l;
+            if (row < p.M) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = m0 + wm * WM + i * 32 + 8 * (v >> 2) + row_l + (v & 3);
-                if (row < p.M) {
+                for (int j = 0; j < NI; ++j)
 #pragma unroll
-                    for (int j = 0; j < NI; ++j) {
-                        const int col = n0 + wn * WN + j * 32 + col_l;
-                        if (col < p.N) out[(int64_t)row * p.N + col] = acc[i][j][v];
+                    for (int g = 0; g < 4; ++g) {
+                        const int col = n0 + wn * WN + j * 32 + 8 * g + col_l;
+                        int32_t* dst = out + (int64_t)row * p.N + col;
+                        if (vec4 && col < p.N) {
+                            *(v4i*)dst = v4i{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (col + e < p.N) dst[e] = acc[i][j][4 * g + e];
+                        }
                     }
-                }
             }
+        }
     } else {
         // The 16-bit tile is staged in LDS (free once the K loop is over) so that global memory is
         // written in whole 512-byte row segments, 16 bytes per lane, instead of 2-byte scatters; the
@@ -363,32 +391,38 @@ __global__ __launch_bounds__(WGM* WGN * 64, 1) void gemm_i8_kernel(const GemmArg
         }
         const float ws = p.x_scale ? p.w_scale[0] : 0.0f;
         const float xs0 = (p.x_scale && !p.per_token) ? p.x_scale[0] : 0.0f;
-        float bj[NI];
-#pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const int col = n0 + wn * WN + j * 32 + col_l;
-            bj[j] = (p.bias && col < p.N) ? p.bias[col] : 0.0f;
-        }
-        // The optional terms are compile-time flags inside the 256-element loop (one uniform switch
-        // outside) so the common cases cost convert + multiply + round + LDS write per element.
+        // The optional terms are compile-time flags inside the loop (one uniform switch outside) so the
+        // common cases cost convert + multiply + round per element and one 8-byte LDS write per four.
         auto phase1 = [&](auto HB, auto RL, auto HR) {
             constexpr bool has_bias = decltype(HB)::value, relu = decltype(RL)::value, has_res = decltype(HR)::value;
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
+            for (int i = 0; i < MI; ++i) {
+                const int lrow = wm * WM + i * 32 + row_l;
+                const int row = m0 + lrow;
+                float c;
+                if (p.x_scale) c = (p.per_token ? p.x_scale[row < p.M ? row : p.M - 1] : xs0) * ws;
+                else c = p.alpha;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int lrow = wm * WM + i * 32 + 8 * (v >> 2) + row_l + (v & 3);
-                    const int row = m0 + lrow;
-                    float c;
-                    if (p.x_scale) c = (p.per_token ? p.x_scale[row < p.M ? row : p.M - 1] : xs0) * ws;
-                    else c = p.alpha;
+                for (int j = 0; j < NI; ++j)
 #pragma unroll
-                    for (int j = 0; j < NI; ++j) {
-                        uint16_t* slot = (uint16_t*)(smem + lrow * PITCH + (wn * WN + j * 32 + col_l) * 2);
-                        const uint32_t rb = has_res ? (uint32_t)*slot : 0u;
-                        *slot = (uint16_t)dequant_one<BF16>(acc[i][j][v], c, bj[j], has_bias, relu, rb, has_res);
+                    for (int g = 0; g < 4; ++g) {
+                        const int lcol = wn * WN + j * 32 + 8 * g + col_l;
+                        float bq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                        if constexpr (has_bias) {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) bq[e] = (n0 + lcol + e < p.N) ? p.bias[n0 + lcol + e] : 0.0f;
+                        }
+                        v2u* slot = (v2u*)(smem + lrow * PITCH + lcol * 2);
+                        v2u rb = {0u, 0u};
+                        if constexpr (has_res) rb = *slot;
+                        uint32_t o[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            o[e] = dequant_one<BF16>(acc[i][j][4 * g + e], c, bq[e], has_bias, relu, rb[e >> 1] >> ((e & 1) * 16),
+                                                     has_res);
+                        *slot = v2u{o[0] | (o[1] << 16), o[2] | (o[3] << 16)};
                     }
-                }
+            }
         };
         using T_ = std::true_type;
         using F_ = std::false_type;
@@ -449,6 +483,8 @@ constexpr int kNumCU = 256;
 
 struct Plan {
     int cfg;     // 0: 256x256 (prefill)  1: 128x256  2: 64x256  3: 32x256  4: 256x256 B^T  5: 256x128 B^T  6: 256x192
+                 // 7: 128x128, three workgroups per CU (short K: the output stream dominates)
+                 // 8: 128x128, K <= 128 fetched in one go, four workgroups per CU
     int bm, bn;
     int splits, iters_per_split;
     int tiles_m, tiles_n;
@@ -462,6 +498,22 @@ Plan make_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split,
         pl.bm = 256;
         if (N <= 128) { pl.cfg = 5; pl.bn = 128; }
         else pl.cfg = 4;
+        allow_split = false;
+    }
+    else if (M > 128 && K <= 128) {
+        // The same, with the whole K range fetched in one go and four workgroups per CU.
+        pl.cfg = 8;
+        pl.bm = 128;
+        pl.bn = 128;
+        allow_split = false;
+    }
+    else if (M > 128 && K <= 256) {
+        // Two to four K steps per tile (attention scores, K = head_dim): loading, MFMAs and the epilogue of
+        // one tile cannot overlap each other, so several small workgroups share a CU and overlap between
+        // themselves; the kernel is bound by writing the output.
+        pl.cfg = 7;
+        pl.bm = 128;
+        pl.bn = 128;
         allow_split = false;
     }
     else if (M > 128) {
@@ -515,6 +567,14 @@ void launch_cfg(const Plan& pl, const GemmArgs& a, int batch, hipStream_t st, bo
         case 2: SQ_LAUNCH(64, 256, 1, 4, 7); break;
         case 3: SQ_LAUNCH(32, 256, 1, 4, 8); break;
         case 6: SQ_LAUNCH(256, 192, 4, 2, 4); break;
+        case 8:
+            if (tiled) hipLaunchKernelGGL((gemm_i8_kernel<128, 128, 2, 2, 3, EPI, BF16, LAY_TILED, 4, true>), grid, dim3(256), 0, st, a);
+            else hipLaunchKernelGGL((gemm_i8_kernel<128, 128, 2, 2, 3, EPI, BF16, LAY_ROWS, 4, true>), grid, dim3(256), 0, st, a);
+            break;
+        case 7:
+            if (tiled) hipLaunchKernelGGL((gemm_i8_kernel<128, 128, 2, 2, 3, EPI, BF16, LAY_TILED, 3>), grid, dim3(256), 0, st, a);
+            else hipLaunchKernelGGL((gemm_i8_kernel<128, 128, 2, 2, 3, EPI, BF16, LAY_ROWS, 3>), grid, dim3(256), 0, st, a);
+            break;
         default:
             if constexpr (EPI == EPI_DEQUANT) {
                 if (pl.cfg == 4) hipLaunchKernelGGL((gemm_i8_kernel<256, 256, 2, 2, 4, EPI, BF16, LAY_BT>), grid, dim3(256), 0, st, a);

@@ -16,6 +16,12 @@ template <bool BF16> SQ_DEVICE void unpack8r(const v4u raw, float (&f)[8])
     }
 }
 
+// e^x for x <= 0 through the hardware 2^x instruction (v_exp_f32): about 3 ulp of fp32 where the result
+// matters (x > -6), far below the half-ulp of the 16-bit rounding that follows; results below 2^-126 come
+// out as 0, which is what their codes are anyway.  The library routine costs ~20 instructions per call and
+// made this pass ALU-bound.
+SQ_DEVICE float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896340736f); }
+
 SQ_DEVICE float block_max_r(float v, float* red)
 {
     v = wave_max(v);
@@ -67,7 +73,7 @@ __global__ __launch_bounds__(256) void softmax_quant_kernel(const uint16_t* __re
         if (idx < nvec) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                z[i][e] = expf(z[i][e] - mx);
+                z[i][e] = fast_exp(z[i][e] - mx);
                 sum += z[i][e];
             }
         }
@@ -83,6 +89,60 @@ __global__ __launch_bounds__(256) void softmax_quant_kernel(const uint16_t* __re
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 // probability rounded to the 16-bit type first (the softmax output is a 16-bit tensor)
+                const float p16 = load16_bits<BF16>(store16_bits<BF16>(z[i][e] * inv));
+                q[e] = round_code(p16 * 127.0f);
+            }
+            __builtin_nontemporal_store(pack8(q), out + idx);
+        }
+    }
+}
+
+// One row per wave (rows up to 4096 scores): four rows per 256-thread workgroup, the reductions are
+// cross-lane shuffles only (no barriers), and every lane keeps NV 16-byte loads in flight, which is what a
+// pass bound by HBM latency x bandwidth needs (a 256-thread workgroup per 4 KB row had 16 bytes per lane).
+template <bool BF16, int NV>
+__global__ __launch_bounds__(256) void softmax_quant_wave_kernel(const uint16_t* __restrict__ s, int64_t rows, int cols,
+                                                                int8_t* __restrict__ pq)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const v4u* sr = (const v4u*)(s + row * (int64_t)cols);
+    const int nvec = cols >> 3;
+    float z[NV][8];
+    float mx = -__builtin_inff();
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = lane + i * 64;
+        if (idx < nvec) {
+            unpack8r<BF16>(__builtin_nontemporal_load(sr + idx), z[i]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) mx = __builtin_fmaxf(mx, z[i][e]);
+        }
+    }
+    mx = wave_max(mx);
+    float sum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = lane + i * 64;
+        if (idx < nvec) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                z[i][e] = fast_exp(z[i][e] - mx);
+                sum += z[i][e];
+            }
+        }
+    }
+    sum = wave_sum(sum);
+    const float inv = 1.0f / sum;
+    v2u* out = (v2u*)(pq + row * (int64_t)cols);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = lane + i * 64;
+        if (idx < nvec) {
+            int q[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
                 const float p16 = load16_bits<BF16>(store16_bits<BF16>(z[i][e] * inv));
                 q[e] = round_code(p16 * 127.0f);
             }
@@ -172,12 +232,16 @@ sq_status sq_softmax_quant_p(const void* s, sq_dtype dtype, int64_t rows, int64_
     const int nvec = (int)(cols >> 3);
     const uint16_t* sp = (const uint16_t*)s;
 #define SQ_SM(BF, NV) hipLaunchKernelGGL((softmax_quant_kernel<BF, NV>), dim3((unsigned)rows), dim3(256), 0, st, sp, (int)cols, pq)
+#define SQ_SMW(BF, NV) hipLaunchKernelGGL((softmax_quant_wave_kernel<BF, NV>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, sp, rows, (int)cols, pq)
     if (dtype == SQ_BF16) {
-        if (nvec <= 256) SQ_SM(true, 1); else if (nvec <= 512) SQ_SM(true, 2); else if (nvec <= 1024) SQ_SM(true, 4); else SQ_SM(true, 8);
+        if (nvec <= 64) SQ_SMW(true, 1); else if (nvec <= 128) SQ_SMW(true, 2); else if (nvec <= 256) SQ_SMW(true, 4);
+        else if (nvec <= 512) SQ_SMW(true, 8); else if (nvec <= 1024) SQ_SM(true, 4); else SQ_SM(true, 8);
     } else {
-        if (nvec <= 256) SQ_SM(false, 1); else if (nvec <= 512) SQ_SM(false, 2); else if (nvec <= 1024) SQ_SM(false, 4); else SQ_SM(false, 8);
+        if (nvec <= 64) SQ_SMW(false, 1); else if (nvec <= 128) SQ_SMW(false, 2); else if (nvec <= 256) SQ_SMW(false, 4);
+        else if (nvec <= 512) SQ_SMW(false, 8); else if (nvec <= 1024) SQ_SM(false, 4); else SQ_SM(false, 8);
     }
 #undef SQ_SM
+#undef SQ_SMW
     return sq_launch_status();
 }
 
