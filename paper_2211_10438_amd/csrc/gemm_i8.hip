@@ -56,15 +56,17 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
     constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
     constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE = A_BYTES + B_BYTES;
     constexpr int RBA = BM / 16, RBB = BN / 16;  // 16-row blocks per operand tile
-    constexpr int SA = (RBA + NW - 1) / NW, SB = BT ? 0 : (RBB + NW - 1) / NW;
-    constexpr int KR = BT ? BN / 16 : 0;  // BT: each lane moves a KR (k) x 4 (n) byte block per stage
-    constexpr int LPS = SA + SB + KR;     // vector-memory loads per wave per stage
-    static_assert(!BT || (NW == 4 && (BN == 256 || BN == 128)), "transposed-B path assumes 256 lanes");
+    constexpr int SA = (RBA + NW - 1) / NW, SB = (RBB + NW - 1) / NW;  // BT: SB raw 1 KB blocks of the [64, BN] B tile
+    constexpr int KR = BT ? BN / 16 : 0;  // BT: each lane transposes a KR (k) x 4 (n) byte block per stage
+    constexpr int LPS = SA + SB;          // vector-memory loads per wave per stage
+    static_assert(!BT || (NW == 4 && BN == 128 && RBB % NW == 0), "transposed-B path assumes 256 lanes and 128 columns");
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
-    static_assert(NSTAGE >= 3 && (NSTAGE - 2) * LPS <= 63, "pipeline depth exceeds the 6-bit vmcnt");
+    static_assert(NSTAGE >= (BT ? 4 : 3) && (NSTAGE - 2) * LPS <= 63, "pipeline depth exceeds the 6-bit vmcnt");
     static_assert(NSTAGE * STAGE <= 160 * 1024, "LDS budget");
     constexpr int EPI_BYTES = EPI == EPI_DEQUANT ? BM * (BN * 2 + 16) : 0;
-    constexpr int RING_BYTES = (ONESHOT ? NSTAGE - 1 : NSTAGE) * STAGE;
+    // BT: behind the ring, three buffers hold the B tile in MFMA operand layout (see transpose_stage).
+    constexpr int BOP = NSTAGE * STAGE;
+    constexpr int RING_BYTES = (ONESHOT ? NSTAGE - 1 : NSTAGE) * STAGE + (BT ? 3 * B_BYTES : 0);
     constexpr int SMEM_BYTES = RING_BYTES > EPI_BYTES ? RING_BYTES : EPI_BYTES;
     static_assert(!ONESHOT || !BT, "one-shot loading is not combined with the transposed-B path");
     static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
@@ -77,18 +79,25 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
     // ---- which tile: hardware deals consecutive workgroup ids round-robin to the 8 XCDs; give
     // each XCD a contiguous range of the logical order, and make that order walk groups of 8
     // m-tiles column by column so that concurrently running tiles share operand rows in L2.
-    const int total = gridDim.x;
-    int pid;
+    // Batched launches (attention heads) are enumerated the same way over (batch, tile) jointly: an XCD
+    // then works through whole heads, and the tiles of a head that share its Q / K / V rows run together.
+    const int64_t total = (int64_t)gridDim.x * gridDim.y;
+    int64_t pid;
     {
-        const int wg = blockIdx.x, xcd = wg & 7, j = wg >> 3;
-        const int q = total >> 3, r = total & 7;
+        const int64_t wg = (int64_t)blockIdx.y * gridDim.x + blockIdx.x, j = wg >> 3;
+        const int xcd = (int)(wg & 7);
+        const int64_t q = total >> 3;
+        const int r = (int)(total & 7);
         pid = xcd * q + (xcd < r ? xcd : r) + j;
     }
     const int tiles = p.tiles_m * p.tiles_n;
-    const int split = pid / tiles;
+    const int per_batch = (int)gridDim.x;  // tiles * splits
+    const int batch = (int)(pid / per_batch);
+    const int pin = (int)(pid - (int64_t)batch * per_batch);
+    const int split = pin / tiles;
     int tm, tn;
     {
-        const int t = pid - split * tiles;
+        const int t = pin - split * tiles;
         constexpr int GM = 8;
         const int per_group = GM * p.tiles_n;
         const int g = t / per_group, first_m = g * GM;
@@ -97,7 +106,6 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
         tm = first_m + in % gsz;
         tn = in / gsz;
     }
-    const int batch = blockIdx.y;
     const int m0 = tm * BM, n0 = tn * BN;
     const int nk_total = (p.K + BK - 1) / BK;
     const int kbeg = split * p.iters_per_split;
@@ -133,8 +141,19 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
         }
         ldsA[i] = rb * 1024;
     }
+    // BT: raw block (i*NW + wave) holds 1024/BN consecutive k rows of the stage, BN/16 lanes per row.
+    int rawrow[SB + 1], rawcol = 0;
+    if constexpr (BT) {
+        rawcol = (lane % (BN / 16)) * 16;
+        if (n0 + rawcol + 16 > p.N) rawcol = p.N - 16 - n0;  // ragged N tile: re-read valid columns (N % 16 == 0)
 #pragma unroll
-    for (int i = 0; i < SB; ++i) {
+        for (int i = 0; i < SB; ++i) {
+            rawrow[i] = (i * NW + wave) * (1024 / BN) + lane / (BN / 16);
+            ldsB[i] = A_BYTES + (i * NW + wave) * 1024;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < (BT ? 0 : SB); ++i) {
         const int rb = (i * NW + wave) % RBB;
         if constexpr (TILED) {
             const int last_rb = (p.N - 1 - n0) >> 4;
@@ -159,30 +178,34 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
 #pragma unroll
         for (int i = 0; i < SA; ++i)
             __builtin_amdgcn_global_load_lds(GPTR(a + (offA[i] - back)), LPTR(base + ldsA[i]), 16, 0, 0);
-#pragma unroll
-        for (int i = 0; i < SB; ++i)
-            __builtin_amdgcn_global_load_lds(GPTR(b + (offB[i] - back)), LPTR(base + ldsB[i]), 16, 0, 0);
-    };
-
-    // ---- transposed-B path: lane block = KR consecutive k rows x 4 consecutive n columns.
-    uint32_t breg[KR + 1];
-    const int bt_cg = BT ? (int)(threadIdx.x % (BN / 4)) : 0;   // column group: columns 4*cg .. 4*cg+3
-    const int bt_ks = BT ? (int)(threadIdx.x / (BN / 4)) : 0;   // k slab: rows ks*KR .. ks*KR+KR-1 of the stage
-    int bt_col = bt_cg * 4;
-    if (BT && n0 + bt_col + 4 > p.N) bt_col = p.N - 4 - n0;      // ragged N tile: re-read valid columns
-    auto load_b = [&](int kt) {
         if constexpr (BT) {
-            const int k0 = (kbeg + kt) * BK + bt_ks * KR;
+            // raw [64, BN] tile of B = [K, N]; rows past K (K tail) re-read row K-1, where the A fragments are zero
 #pragma unroll
-            for (int j = 0; j < KR; ++j) {
-                int k = k0 + j;
-                k = k < p.K ? k : p.K - 1;  // K tail: any valid row (the A fragments there are zero)
-                breg[j] = *(const uint32_t*)(Bb + (int64_t)k * p.ldb + bt_col);
+            for (int i = 0; i < SB; ++i) {
+                int k = (kbeg + kt) * BK + rawrow[i];
+                k = k < p.K ? k : p.K - 1;
+                __builtin_amdgcn_global_load_lds(GPTR(Bb + (int64_t)k * p.ldb + rawcol), LPTR(base + ldsB[i]), 16, 0, 0);
             }
+        } else {
+#pragma unroll
+            for (int i = 0; i < SB; ++i)
+                __builtin_amdgcn_global_load_lds(GPTR(b + (offB[i] - back)), LPTR(base + ldsB[i]), 16, 0, 0);
         }
     };
-    auto store_b = [&](int buf) {
+
+    // ---- transposed-B path.  The raw [64 k, BN n] tile of a stage arrives in the ring like A does (LDS-DMA,
+    // NSTAGE deep, so no global-memory latency sits in the K loop).  One K step before a stage is consumed
+    // every lane reads a KR (k) x 4 (n) byte block of it from LDS, transposes it bytewise in registers
+    // (v_perm_b32) and writes it, n-major, into one of three operand-layout buffers behind the ring; the
+    // MFMA loop then reads B fragments from there exactly as it reads them from the ring otherwise.
+    const int bt_cg = BT ? (int)(threadIdx.x % (BN / 4)) : 0;   // column group: columns 4*cg .. 4*cg+3
+    const int bt_ks = BT ? (int)(threadIdx.x / (BN / 4)) : 0;   // k slab: rows ks*KR .. ks*KR+KR-1 of the stage
+    auto transpose_stage = [&](int ring_buf, int op_buf) {
         if constexpr (BT) {
+            const char* raw = smem + ring_buf * STAGE + A_BYTES + (bt_ks * KR) * BN + bt_cg * 4;
+            uint32_t breg[KR + 1];
+#pragma unroll
+            for (int j = 0; j < KR; ++j) breg[j] = *(const uint32_t*)(raw + j * BN);
             // 4x4 byte transposes: out[e][m] = bytes e of rows 4m .. 4m+3
             uint32_t out[4][KR / 4 + 1];
 #pragma unroll
@@ -195,17 +218,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
                 out[2][m] = __builtin_amdgcn_perm(u1, t1, 0x05040100u);
                 out[3][m] = __builtin_amdgcn_perm(u1, t1, 0x07060302u);
             }
-            char* base = smem + buf * STAGE + A_BYTES;
+            char* base = smem + BOP + op_buf * B_BYTES;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int n = bt_cg * 4 + e, r = n & 15;
-                if constexpr (KR == 16) {
-                    const int pos = bt_ks ^ swz(r);
-                    *(v4u*)(base + (n >> 4) * 1024 + r * 64 + pos * 16) = v4u{out[e][0], out[e][1], out[e][2], out[e][3]};
-                } else {
-                    const int pos = (bt_ks >> 1) ^ swz(r);
-                    *(v2u*)(base + (n >> 4) * 1024 + r * 64 + pos * 16 + (bt_ks & 1) * 8) = v2u{out[e][0], out[e][1]};
-                }
+                const int pos = (bt_ks >> 1) ^ swz(r);  // KR = 8: a lane holds half a 16-byte chunk
+                *(v2u*)(base + (n >> 4) * 1024 + r * 64 + pos * 16 + (bt_ks & 1) * 8) = v2u{out[e][0], out[e][1]};
             }
         }
     };
@@ -216,7 +234,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
     const int frow = lane & 15;
     const int lane_off = ((lane & 31) >> 4) * 1024 + frow * 64 + (((lane >> 5) ^ swz(frow)) * 16);
     const int fragA0 = wm * (WM / 16) * 1024 + lane_off;
-    const int fragB0 = A_BYTES + wn * (WN / 16) * 1024 + lane_off;
+    const int fragB0 = (BT ? 0 : A_BYTES) + wn * (WN / 16) * 1024 + lane_off;
 
     v4i fa0[MI], fb0[NI], fa1[MI], fb1[NI];
     v16i acc[MI][NI];
@@ -227,9 +245,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-    auto read_frags = [&](v4i(&fa)[MI], v4i(&fb)[NI], int buf, int kk) {
+    auto read_frags = [&](v4i(&fa)[MI], v4i(&fb)[NI], int buf, int kk, int op_buf) {
         const char* sa = smem + buf * STAGE + (fragA0 ^ (kk * 32));
-        const char* sb = smem + buf * STAGE + (fragB0 ^ (kk * 32));
+        const char* sb = smem + (BT ? BOP + op_buf * B_BYTES : buf * STAGE) + (fragB0 ^ (kk * 32));
 #pragma unroll
         for (int i = 0; i < MI; ++i) fa[i] = *(const v4i*)(sa + i * 2048);
 #pragma unroll
@@ -278,45 +296,42 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
     if constexpr (ONESHOT) {
         wait_vmcnt_imm<0>();
     } else if constexpr (BT) {
-        // B stages 0 and 1 go through registers synchronously (which also drains the DMA loads above);
-        // stage 2 stays in registers and is written to LDS during K step 0.
-        load_b(0);
-        store_b(0);
-        load_b(1 < nk ? 1 : nk - 1);
-        store_b(1);
-        load_b(2 < nk ? 2 : nk - 1);
-        wait_vmcnt_imm<KR>();
+        // stages 0 and 1 landed; their B tiles go to operand buffers 0 and 1
+        wait_vmcnt_imm<(NSTAGE - 3) * LPS>();
+        __builtin_amdgcn_s_barrier();
+        transpose_stage(0, 0);
+        transpose_stage(1, 1);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     } else {
         wait_vmcnt_imm<(NSTAGE - 2) * LPS>();
     }
     __builtin_amdgcn_s_barrier();
-    read_frags(fa0, fb0, 0, 0);
+    read_frags(fa0, fb0, 0, 0, 0);
 
-    int buf = 0;
+    int buf = 0, ob = 0;  // ring buffer and operand buffer of the current K step
     for (int it = 0; it < nk - 1; ++it) {
         // first half of K step `it`
-        read_frags(fa1, fb1, buf, 1);
+        read_frags(fa1, fb1, buf, 1, ob);
         mfma_all(fa0, fb0);
         interleave_hint(std::integral_constant<int, 0>{});
         // second half; meanwhile make stage it+1 visible and refill the buffer freed by step it-1
         const int nbuf = buf + 1 == NSTAGE ? 0 : buf + 1;
+        const int nob = ob == 2 ? 0 : ob + 1;
         if constexpr (!ONESHOT) {
-            wait_vmcnt_imm<(NSTAGE - 3) * LPS>();
+            // BT needs stage it+2 landed (its B tile is transposed now, for the step after next)
+            wait_vmcnt_imm<(NSTAGE - (BT ? 4 : 3)) * LPS>();
             __builtin_amdgcn_s_barrier();
-            if constexpr (BT) {
-                store_b(buf + 2 >= NSTAGE ? buf + 2 - NSTAGE : buf + 2);
-                load_b(it + 3 < nk ? it + 3 : nk - 1);
-            }
+            if constexpr (BT) transpose_stage(buf + 2 >= NSTAGE ? buf + 2 - NSTAGE : buf + 2, ob == 0 ? 2 : ob - 1);
             issue_stage(it + NSTAGE - 1 < nk ? it + NSTAGE - 1 : nk - 1, buf == 0 ? NSTAGE - 1 : buf - 1);
         }
-        read_frags(fa0, fb0, nbuf, 0);
+        read_frags(fa0, fb0, nbuf, 0, nob);
         mfma_all(fa1, fb1);
         interleave_hint(std::integral_constant<int, (BT || ONESHOT) ? 0 : SA + SB>{});
         buf = nbuf;
+        ob = nob;
     }
     // last K step
-    read_frags(fa1, fb1, buf, 1);
+    read_frags(fa1, fb1, buf, 1, ob);
     if (has_tail) {
         // chunk index of this lane inside the 64-byte step: kk*2 + (lane >> 5)
         const int c0 = lane >> 5, c1 = 2 + (lane >> 5);
@@ -496,8 +511,8 @@ Plan make_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split,
     pl.bn = 256;
     if (b_transposed) {
         pl.bm = 256;
-        if (N <= 128) { pl.cfg = 5; pl.bn = 128; }
-        else pl.cfg = 4;
+        pl.cfg = 5;
+        pl.bn = 128;
         allow_split = false;
     }
     else if (M > 128 && K <= 128) {
@@ -577,8 +592,7 @@ void launch_cfg(const Plan& pl, const GemmArgs& a, int batch, hipStream_t st, bo
             break;
         default:
             if constexpr (EPI == EPI_DEQUANT) {
-                if (pl.cfg == 4) hipLaunchKernelGGL((gemm_i8_kernel<256, 256, 2, 2, 4, EPI, BF16, LAY_BT>), grid, dim3(256), 0, st, a);
-                else hipLaunchKernelGGL((gemm_i8_kernel<256, 128, 4, 1, 5, EPI, BF16, LAY_BT>), grid, dim3(256), 0, st, a);
+                hipLaunchKernelGGL((gemm_i8_kernel<256, 128, 4, 1, 5, EPI, BF16, LAY_BT>), grid, dim3(256), 0, st, a);
             }
             break;
     }
