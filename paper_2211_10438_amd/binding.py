@@ -161,9 +161,21 @@ def prepare_weight(w: torch.Tensor, s: torch.Tensor | None = None, workspace=Non
 
 def quantize_act(x: torch.Tensor, mode: int, inv_s: torch.Tensor | None = None, static_scale: torch.Tensor | None = None,
                  c_i: int | None = None, out=None, workspace=None, layout: int = ROW_MAJOR):
-    """x [t, ldx] -> (xq int8 [t, c_i], scale fp32 [t] or [1]).  ``c_i`` < ldx quantizes a column prefix."""
-    t, ldx = x.shape
-    c_i = ldx if c_i is None else c_i
+    """x [t, ldx] -> (xq int8 [t, c_i], scale fp32 [t] or [1]).  ``c_i`` < ldx quantizes a column prefix; a
+    column slice of a wider matrix (unit column stride, row stride >= its width) is taken in place: its row
+    stride becomes ldx."""
+    if x.dim() != 2 or not x.is_cuda:
+        raise SqmiError("x must be a 2-D GPU tensor")
+    if x.is_contiguous():
+        t, ldx = x.shape
+        c_i = ldx if c_i is None else c_i
+        x_ptr = x.data_ptr()
+    else:
+        if x.stride(1) != 1 or x.stride(0) < x.shape[1]:
+            raise SqmiError("x must be contiguous or a column slice of a contiguous matrix")
+        t, ldx = x.shape[0], x.stride(0)
+        c_i = x.shape[1] if c_i is None else c_i
+        x_ptr = x.data_ptr()
     if out is None:
         xq = empty_codes(t, c_i, layout, x.device)
         if mode == PER_TENSOR_STATIC:
@@ -176,7 +188,7 @@ def quantize_act(x: torch.Tensor, mode: int, inv_s: torch.Tensor | None = None, 
         xq, scale = out
     wp, wb, keep = _workspace(workspace_bytes(OP_QUANTIZE_ACT, t, c_i, 0) if mode == PER_TENSOR_DYNAMIC else 0,
                               x.device, workspace)
-    _check(lib().sq_quantize_act(_dev(x, None, "x"), _dt(x), t, c_i, ldx, _opt(inv_s, torch.float32, "inv_s"), mode,
+    _check(lib().sq_quantize_act(x_ptr, _dt(x), t, c_i, ldx, _opt(inv_s, torch.float32, "inv_s"), mode,
                                  _dev(scale, torch.float32, "scale"), _dev(xq, torch.int8, "xq"), layout, wp, wb,
                                  _stream()), "sq_quantize_act")
     return xq, scale

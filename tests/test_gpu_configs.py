@@ -172,3 +172,141 @@ def test_config4_int8_attention_bmms():
         ref = oracle.w8a8_bmm(pq[h:h + 1].cpu().numpy(), codes[2][h:h + 1].cpu().numpy(), False, alpha2, F16)
         assert ulp_distance(bits_from_dev(o[h]), ref[0]).max() <= 1, f"head {h}"
     assert bool(torch.isfinite(o.float()).all())
+
+
+def test_config5_opt66b_decoder_layer_chain():
+    """OPT-66B-shaped decoder layer, batch 4 x sequence 1024 (hidden 9216, FFN 36864, 72 heads), alpha 0.8,
+    1% outlier channels x60: LayerNorm with the smoothing factors folded into gamma / beta + per-token
+    quantization -> QKV GEMM -> INT8 attention (Q K^T, softmax + P quantization, P V) -> out-proj + residual
+    -> LayerNorm + quantization -> FC1 + ReLU -> FC2 + residual.  Every stage runs on the GPU on the previous
+    stage's GPU output; each stage is checked against the oracle fed with that same input, on sampled rows /
+    heads (exact gates for the GEMMs and quantizers, the +-1 code gate for LayerNorm and softmax).  Head
+    splitting / merging between the stages is a torch permute (layout plumbing, no arithmetic)."""
+    hid, ffn, n_head, bsz, seq, alpha = 9216, 36864, 72, 4, 1024, 0.8
+    d_head, t = hid // n_head, bsz * seq
+    g = torch.Generator(device="cuda")
+    g.manual_seed(synth.BASE_SEED + 500)
+
+    def dev_weight(c_i, c_o):
+        w = torch.empty((c_i, c_o), device="cuda", dtype=torch.float16)
+        for r0 in range(0, c_i, 2048):
+            w[r0:r0 + 2048] = (torch.randn((min(2048, c_i - r0), c_o), generator=g, device="cuda") * 0.02).to(torch.float16)
+        return w
+
+    def ln_params(seed):
+        ch = synth.outlier_channels(hid, synth.n_outlier_channels(hid, 0.01), seed)
+        gamma = np.ones(hid, np.float32)
+        gamma[ch] = 60.0  # the LayerNorm output (what the paper smooths) gets its outlier channels from gamma
+        beta = (np.random.default_rng(seed + 1).standard_normal(hid) * 0.1).astype(np.float32)
+        return gamma, beta
+
+    def smoothed_layer(x16, gamma, beta, w):
+        """Offline part for a LayerNorm -> linear pair: calibrate on 512 tokens, Eq. 4, fold into gamma / beta."""
+        xc = torch.nn.functional.layer_norm(x16[:512].float(), (hid,), torch.from_numpy(gamma).cuda(),
+                                            torch.from_numpy(beta).cuda(), 1e-5).to(torch.float16)
+        s, inv_s = sq.smooth_scales(sq.act_absmax_per_channel(xc).cpu(), sq.weight_absmax_per_in_channel(w).cpu(), alpha)
+        wq, ws = sq.prepare_weight(w, s.cuda())
+        inv = inv_s.numpy()
+        return wq, ws, (gamma * inv).astype(np.float32), (beta * inv).astype(np.float32)
+
+    def check_linear(name, xq, xs, wq, ws, y, bias, res, relu, seed):
+        rows = _sample_rows(t, 6, seed)
+        ref = oracle.w8a8_linear(xq.cpu().numpy(), xs.cpu().numpy(), wq.cpu().numpy(), ws.cpu().numpy(), F16,
+                                 bias=bias, residual_bits=None if res is None else bits_from_dev(res), relu=relu, rows=rows)
+        dd = ulp_distance(bits_from_dev(y[torch.from_numpy(rows).cuda()]), ref[rows])
+        assert dd.max() <= 1 and (dd == 0).mean() > 0.999, f"{name}: max ulp {dd.max()}"
+
+    def check_ln(name, x16, gamma_f, beta_f, xq, xs, seed):
+        rows = _sample_rows(t, 8, seed)
+        q_ref, s_ref = oracle.ln_quantize(bits_from_dev(x16[torch.from_numpy(rows).cuda()]), F16, gamma_f, beta_f)
+        q = xq[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.int32)
+        assert np.abs(q - q_ref.astype(np.int32)).max() <= 1 and (q != q_ref).mean() <= 2e-3, name
+        assert np.allclose(xs[torch.from_numpy(rows).cuda()].cpu().numpy(), s_ref, rtol=1e-5), name
+
+    def check_quant(name, x16, xq, xs, seed):
+        rows = _sample_rows(t, 8, seed)
+        q_ref, s_ref = oracle.quantize_act(bits_from_dev(x16[torch.from_numpy(rows).cuda()]), F16, oracle.PER_TOKEN_DYNAMIC)
+        assert np.array_equal(xq[torch.from_numpy(rows).cuda()].cpu().numpy(), q_ref), name
+        assert np.array_equal(xs[torch.from_numpy(rows).cuda()].cpu().numpy(), s_ref), name
+
+    _progress("config 5: inputs and offline preparation")
+    x = torch.randn((t, hid), generator=g, device="cuda").to(torch.float16)
+    gamma1, beta1 = ln_params(synth.BASE_SEED + 510)
+    w = dev_weight(hid, 3 * hid)
+    wq_qkv, ws_qkv, g1f, b1f = smoothed_layer(x, gamma1, beta1, w)
+    w = dev_weight(hid, hid)
+    wq_o, ws_o = sq.prepare_weight(w, None)
+    del w
+    bias_qkv, bias_o = synth.bias(3 * hid, 520), synth.bias(hid, 521)
+    bias_1, bias_2 = synth.bias(ffn, 522), synth.bias(hid, 523)
+
+    _progress("config 5: LayerNorm 1 + quantize")
+    xq, xs = sq.ln_quantize(x, dev(g1f), dev(b1f))
+    check_ln("ln1", x, g1f, b1f, xq, xs, 530)
+    _progress("config 5: QKV projection")
+    qkv = sq.w8a8_linear(xq, xs, wq_qkv, ws_qkv, torch.float16, bias=dev(bias_qkv))
+    check_linear("qkv", xq, xs, wq_qkv, ws_qkv, qkv, bias_qkv, None, False, 531)
+    del wq_qkv
+
+    _progress("config 5: per-tensor quantization of Q, K, V and head split")
+    codes, steps = [], []
+    for i in range(3):
+        part = qkv[:, i * hid:(i + 1) * hid]  # [t, hid] view with row stride 3*hid
+        cq, cs = sq.quantize_act(part, sq.PER_TENSOR_DYNAMIC)
+        rows = _sample_rows(t, 4, 540 + i)
+        ref, _ = oracle.quantize_act(bits_from_dev(part[torch.from_numpy(rows).cuda()].contiguous()), F16,
+                                     oracle.PER_TENSOR_STATIC, static_scale=np.float32(cs.item()))
+        assert np.array_equal(cq[torch.from_numpy(rows).cuda()].cpu().numpy(), ref), f"qkv part {i}"
+        codes.append(cq.view(bsz, seq, n_head, d_head).permute(0, 2, 1, 3).contiguous().view(bsz * n_head, seq, d_head))
+        steps.append(np.float32(cs.item()))
+    del qkv
+    heads = [0, 131, bsz * n_head - 1]
+    _progress("config 5: attention")
+    alpha1 = float(np.float32(steps[0] * steps[1]) / np.float32(np.sqrt(np.float32(d_head))))
+    sc = sq.w8a8_bmm(codes[0], codes[1], True, alpha1, torch.float16)
+    for h in heads:
+        ref = oracle.w8a8_bmm(codes[0][h:h + 1].cpu().numpy(), codes[1][h:h + 1].cpu().numpy(), True, alpha1, F16)
+        assert ulp_distance(bits_from_dev(sc[h]), ref[0]).max() <= 1, f"scores head {h}"
+    pq = sq.softmax_quant_p(sc)
+    for h in heads:
+        ref = oracle.softmax_quant_p(bits_from_dev(sc[h]), F16).astype(np.int32)
+        diff = np.abs(pq[h].cpu().numpy().astype(np.int32) - ref)
+        assert diff.max() <= 1 and (diff != 0).mean() <= 1e-3, f"P head {h}"
+    del sc
+    alpha2 = float(np.float32(steps[2]) / np.float32(127.0))
+    o = sq.w8a8_bmm(pq, codes[2], False, alpha2, torch.float16)
+    for h in heads:
+        ref = oracle.w8a8_bmm(pq[h:h + 1].cpu().numpy(), codes[2][h:h + 1].cpu().numpy(), False, alpha2, F16)
+        assert ulp_distance(bits_from_dev(o[h]), ref[0]).max() <= 1, f"O head {h}"
+    del pq, codes
+    attn = o.view(bsz, n_head, seq, d_head).permute(0, 2, 1, 3).contiguous().view(t, hid)
+    del o
+
+    _progress("config 5: out-proj + residual")
+    aq, as_ = sq.quantize_act(attn, sq.PER_TOKEN_DYNAMIC)
+    check_quant("attn quant", attn, aq, as_, 550)
+    h1 = sq.w8a8_linear(aq, as_, wq_o, ws_o, torch.float16, bias=dev(bias_o), residual=x)
+    check_linear("out_proj", aq, as_, wq_o, ws_o, h1, bias_o, x, False, 551)
+    del attn, aq, wq_o
+
+    _progress("config 5: LayerNorm 2 + FC1 + ReLU")
+    gamma2, beta2 = ln_params(synth.BASE_SEED + 560)
+    w = dev_weight(hid, ffn)
+    wq_1, ws_1, g2f, b2f = smoothed_layer(h1, gamma2, beta2, w)
+    del w
+    hq, hs = sq.ln_quantize(h1, dev(g2f), dev(b2f))
+    check_ln("ln2", h1, g2f, b2f, hq, hs, 561)
+    f1 = sq.w8a8_linear(hq, hs, wq_1, ws_1, torch.float16, bias=dev(bias_1), relu=True)
+    check_linear("fc1", hq, hs, wq_1, ws_1, f1, bias_1, None, True, 562)
+    del wq_1, hq
+
+    _progress("config 5: FC2 + residual")
+    w = dev_weight(ffn, hid)
+    wq_2, ws_2 = sq.prepare_weight(w, None)
+    del w
+    fq, fs = sq.quantize_act(f1, sq.PER_TOKEN_DYNAMIC)
+    check_quant("fc1 out quant", f1, fq, fs, 570)
+    assert int(fq.min().item()) >= 0  # ReLU output: only the non-negative half of the code range
+    out = sq.w8a8_linear(fq, fs, wq_2, ws_2, torch.float16, bias=dev(bias_2), residual=h1)
+    check_linear("fc2", fq, fs, wq_2, ws_2, out, bias_2, h1, False, 571)
+    assert bool(torch.isfinite(out.float()).all())
