@@ -123,15 +123,15 @@ def weight_absmax_per_in_channel(w_bits, dtype: int):
     return out
 
 
-def prepare_weight(w_bits, dtype: int, s=None):
-    """W [c_i, c_o] -> (wq int8 [c_o, c_i], Delta_W fp32 scalar)."""
+def prepare_weight(w_bits, dtype: int, s=None, per_channel: bool = False):
+    """W [c_i, c_o] -> (wq int8 [c_o, c_i], Delta_W fp32 [1], or [c_o] with per_channel)."""
     w = _c(bits16(w_bits), np.uint16)
     c_i, c_o = w.shape
     s = _c(s, np.float32)
     wq = np.empty((c_o, c_i), np.int8)
-    ws = np.empty(1, np.float32)
-    _chk(lib().orc_prepare_weight(_p(w), dtype, _p(s), ctypes.c_int64(c_i), ctypes.c_int64(c_o), _p(wq), _p(ws)),
-         "prepare_weight")
+    ws = np.empty(c_o if per_channel else 1, np.float32)
+    fn = lib().orc_prepare_weight_per_channel if per_channel else lib().orc_prepare_weight
+    _chk(fn(_p(w), dtype, _p(s), ctypes.c_int64(c_i), ctypes.c_int64(c_o), _p(wq), _p(ws)), "prepare_weight")
     return wq, ws
 
 

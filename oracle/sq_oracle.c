@@ -192,6 +192,33 @@ int orc_prepare_weight(const uint16_t* w, int dtype, const float* s, int64_t c_i
     return 0;
 }
 
+/* Per-output-channel weight quantization (the weight granularity of Table 7): one step per column n of
+   W_hat [c_i, c_o], Delta_W[n] = max_j |W_hat[j, n]| / 127, Wq[n, j] = round(W_hat[j, n] * (127 / max_j|W_hat[j, n]|)).
+   A column of zeros gets step 0 and codes 0. */
+int orc_prepare_weight_per_channel(const uint16_t* w, int dtype, const float* s, int64_t c_i, int64_t c_o,
+                                   int8_t* wq, float* w_scale)
+{
+    if (!w || !wq || !w_scale || c_i <= 0 || c_o <= 0) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < c_o; ++n) {
+        float a = 0.0f;
+        for (int64_t j = 0; j < c_i; ++j) {
+            float v = load16(w + j * c_o + n, dtype);
+            if (s) v = v * s[j];
+            v = fabsf(v);
+            if (v > a) a = v;
+        }
+        w_scale[n] = a / 127.0f;
+        float r = a > 0.0f ? 127.0f / a : 0.0f;
+        for (int64_t j = 0; j < c_i; ++j) {
+            float v = load16(w + j * c_o + n, dtype);
+            if (s) v = v * s[j];
+            wq[n * c_i + j] = round_code(v * r);
+        }
+    }
+    return 0;
+}
+
 /* ---------------------------------------------------------------- Eq. 1 on activations */
 
 static float smoothed(const uint16_t* x, int dtype, const float* inv_s, int64_t j)

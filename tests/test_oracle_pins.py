@@ -210,6 +210,36 @@ def test_prepare_weight_matches_quantizer_on_transposed_smoothed_weight():
     assert not np.array_equal(wq1, wq)
 
 
+def test_prepare_weight_per_channel_pins():
+    """Per-output-channel weight steps (the weight granularity of Table 7)."""
+    c, ax, aw = _case()
+    s, _ = oracle.smooth_scales(ax, aw, 0.5)
+    wq, ws = oracle.prepare_weight(c["w"], F16, s, per_channel=True)
+    assert wq.shape == (80, 96) and ws.shape == (80,)
+    wh = (c["w"].astype(np.float32) * s[:, None]).astype(np.float64)  # W_hat [C_i, C_o]
+    # every column: step = its own absmax / 127, every code within half a step, the extreme code is used
+    assert np.allclose(ws.astype(np.float64) * 127.0, np.abs(wh).max(axis=0), rtol=1e-6)
+    err = np.abs(wh.T - wq.astype(np.float64) * ws[:, None].astype(np.float64))
+    assert np.all(err <= ws[:, None].astype(np.float64) / 2 * (1 + 2.0 ** -12))
+    assert np.all(np.abs(wq).max(axis=1) == 127)
+    # a column equals the per-tensor quantizer run on that column alone (brute force through another function)
+    for n in (0, 17, 79):
+        col = np.ascontiguousarray(c["w"][:, n:n + 1])
+        wq1, ws1 = oracle.prepare_weight(col, F16, s)
+        assert np.array_equal(wq1[0], wq[n]) and ws1[0] == ws[n]
+    # when every column has the same absmax, per-channel and per-tensor agree
+    w2 = c["w"].copy()
+    w2[0, :] = np.float16(8.0)  # dominates every column (|w| ~ 0.02), s = 1
+    a, sa = oracle.prepare_weight(w2, F16, None, per_channel=True)
+    b, sb = oracle.prepare_weight(w2, F16, None)
+    assert np.array_equal(a, b) and np.all(sa == sb[0])
+    # an all-zero column: step 0, codes 0
+    w3 = c["w"].copy()
+    w3[:, 5] = 0
+    z, sz = oracle.prepare_weight(w3, F16, None, per_channel=True)
+    assert sz[5] == 0.0 and not z[5].any()
+
+
 # ------------------------------------------------------------------ integer contraction
 
 def test_int_gemm_brute_force_tiny():
