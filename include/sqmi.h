@@ -94,13 +94,15 @@ sq_status sq_weight_absmax_per_in_channel(const void* w, sq_dtype dtype, int64_t
 
 /* Offline weight preparation (Eq. 3 then Eq. 1, per-tensor as in Table 2):
  *   W_hat = diag(s) W;  Delta_W = max|W_hat| / 127;  Wq = round(W_hat * fl32(127 / max|W_hat|)).
+ * With w_scale_per_channel != 0 the maximum, the step and the rounding are taken per output channel n
+ * (column n of W_hat), the weight granularity of Table 7: Delta_W[n] = max_j |W_hat[j, n]| / 127.
  * w: device [c_i, c_o] row-major 16-bit; s: device fp32 [c_i] or NULL (s = 1);
  * wq: device int8 [c_o, c_i] (transposed: contraction index contiguous) in layout `wq_layout`;
- * w_scale: device fp32 [1].
- * workspace: device, >= sq_workspace_bytes(SQ_OP_PREPARE_WEIGHT, ...) bytes. */
+ * w_scale: device fp32 [1], or [c_o] with w_scale_per_channel.
+ * workspace: device, >= sq_workspace_bytes(SQ_OP_PREPARE_WEIGHT, 0, c_i, c_o) bytes. */
 sq_status sq_prepare_weight(const void* w, sq_dtype dtype, const float* s, int64_t c_i, int64_t c_o,
-                            int8_t* wq, sq_layout wq_layout, float* w_scale, void* workspace,
-                            size_t ws_bytes, void* stream);
+                            int8_t* wq, sq_layout wq_layout, float* w_scale, int w_scale_per_channel,
+                            void* workspace, size_t ws_bytes, void* stream);
 
 /* Activation quantization (Eq. 1; granularities of Table 2).
  * x: device [t, c_i] 16-bit, row stride ldx elements (ldx >= c_i, multiple of 8);
@@ -116,16 +118,16 @@ sq_status sq_quantize_act(const void* x, sq_dtype dtype, int64_t t, int64_t c_i,
 
 /* W8A8 linear layer (Eq. 2) with the dequantizing epilogue fused into the INT8 GEMM:
  *   acc_tn = sum_j xq[t, j] * wq[n, j]                                   (exact int32)
- *   v = fl32(float(acc_tn) * fl32(x_scale_t * w_scale)); v += bias_n; v = max(v, 0) if relu;
+ *   v = fl32(float(acc_tn) * fl32(x_scale_t * w_scale_n)); v += bias_n; v = max(v, 0) if relu;
  *   v += residual_tn;  y_tn = round_to_16bit(v).
  * xq: device int8 [t, c_i]; x_scale: device fp32 [t] if x_scale_per_token else [1];
- * wq: device int8 [c_o, c_i]; w_scale: device fp32 [1];
+ * wq: device int8 [c_o, c_i]; w_scale: device fp32 [c_o] if w_scale_per_channel else [1] (Eq. 2's diag(Delta_W));
  * bias: device fp32 [c_o] or NULL; residual: device [t, c_o] of the output dtype or NULL;
  * y: device [t, c_o] of dtype `out`, row-major.
  * layout: layout of BOTH xq and wq (as produced by sq_quantize_act / sq_prepare_weight).
  * workspace: device, >= sq_workspace_bytes(SQ_OP_W8A8_LINEAR, t, c_i, c_o) bytes (may be 0). */
 sq_status sq_w8a8_linear(const int8_t* xq, const float* x_scale, int x_scale_per_token,
-                         const int8_t* wq, const float* w_scale, const float* bias,
+                         const int8_t* wq, const float* w_scale, int w_scale_per_channel, const float* bias,
                          const void* residual, int relu, void* y, sq_dtype out, int64_t t,
                          int64_t c_i, int64_t c_o, sq_layout layout, void* workspace, size_t ws_bytes,
                          void* stream);

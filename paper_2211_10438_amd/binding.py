@@ -48,9 +48,9 @@ def lib() -> ctypes.CDLL:
         L.sq_smooth_scales.argtypes = [vp, vp, f32, i64, vp, vp]
         L.sq_act_absmax_per_channel.argtypes = [vp, i32, i64, i64, vp, vp]
         L.sq_weight_absmax_per_in_channel.argtypes = [vp, i32, i64, i64, vp, vp]
-        L.sq_prepare_weight.argtypes = [vp, i32, vp, i64, i64, vp, i32, vp, vp, ctypes.c_size_t, vp]
+        L.sq_prepare_weight.argtypes = [vp, i32, vp, i64, i64, vp, i32, vp, i32, vp, ctypes.c_size_t, vp]
         L.sq_quantize_act.argtypes = [vp, i32, i64, i64, i64, vp, i32, vp, vp, i32, vp, ctypes.c_size_t, vp]
-        L.sq_w8a8_linear.argtypes = [vp, vp, i32, vp, vp, vp, vp, i32, vp, i32, i64, i64, i64, i32, vp, ctypes.c_size_t, vp]
+        L.sq_w8a8_linear.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, i32, vp, i32, i64, i64, i64, i32, vp, ctypes.c_size_t, vp]
         L.sq_i8_gemm_i32.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, ctypes.c_size_t, vp]
         L.sq_w8a8_bmm.argtypes = [vp, vp, i32, f32, vp, i32, i64, i64, i64, i64, i64, i64, i64, vp]
         L.sq_softmax_quant_p.argtypes = [vp, i32, i64, i64, vp, vp]
@@ -148,14 +148,16 @@ def weight_absmax_per_in_channel(w: torch.Tensor) -> torch.Tensor:
     return out
 
 
-def prepare_weight(w: torch.Tensor, s: torch.Tensor | None = None, workspace=None, layout: int = ROW_MAJOR):
-    """W [c_i, c_o] (+ optional device fp32 s [c_i]) -> (wq int8 [c_o, c_i] in `layout`, w_scale fp32 [1])."""
+def prepare_weight(w: torch.Tensor, s: torch.Tensor | None = None, workspace=None, layout: int = ROW_MAJOR,
+                   per_channel: bool = False):
+    """W [c_i, c_o] (+ optional device fp32 s [c_i]) -> (wq int8 [c_o, c_i] in `layout`, w_scale fp32 [1], or
+    [c_o] with per_channel: one step per output channel)."""
     c_i, c_o = w.shape
     wq = empty_codes(c_o, c_i, layout, w.device)
-    w_scale = torch.empty(1, dtype=torch.float32, device=w.device)
+    w_scale = torch.empty(c_o if per_channel else 1, dtype=torch.float32, device=w.device)
     wp, wb, keep = _workspace(workspace_bytes(OP_PREPARE_WEIGHT, 0, c_i, c_o), w.device, workspace)
     _check(lib().sq_prepare_weight(_dev(w, None, "w"), _dt(w), _opt(s, torch.float32, "s"), c_i, c_o, wq.data_ptr(),
-                                   layout, w_scale.data_ptr(), wp, wb, _stream()), "sq_prepare_weight")
+                                   layout, w_scale.data_ptr(), int(per_channel), wp, wb, _stream()), "sq_prepare_weight")
     return wq, w_scale
 
 
@@ -196,9 +198,15 @@ def quantize_act(x: torch.Tensor, mode: int, inv_s: torch.Tensor | None = None, 
 
 def w8a8_linear(xq: torch.Tensor, x_scale: torch.Tensor, wq: torch.Tensor, w_scale: torch.Tensor, out_dtype,
                 bias=None, residual=None, relu: bool = False, out=None, workspace=None,
-                layout: int = ROW_MAJOR) -> torch.Tensor:
+                layout: int = ROW_MAJOR, w_per_channel: bool | None = None) -> torch.Tensor:
+    """w_scale: fp32 [1] (per tensor) or [c_o] (per output channel; inferred from its length unless
+    ``w_per_channel`` says otherwise)."""
     t, c_i = xq.shape
     c_o = wq.shape[0]
+    if w_per_channel is None:
+        w_per_channel = w_scale.numel() == c_o and c_o > 1
+    if w_scale.numel() != (c_o if w_per_channel else 1):
+        raise SqmiError("w_scale must have 1 entry, or c_o entries with w_per_channel")
     if wq.shape[1] != c_i:
         raise SqmiError("wq must be [c_o, c_i]")
     if x_scale.numel() not in (1, t):
@@ -207,7 +215,7 @@ def w8a8_linear(xq: torch.Tensor, x_scale: torch.Tensor, wq: torch.Tensor, w_sca
     wp, wb, keep = _workspace(workspace_bytes(OP_W8A8_LINEAR, t, c_i, c_o), xq.device, workspace)
     per_token = int(x_scale.numel() == t)
     _check(lib().sq_w8a8_linear(_dev(xq, torch.int8, "xq"), _dev(x_scale, torch.float32, "x_scale"), per_token,
-                                _dev(wq, torch.int8, "wq"), _dev(w_scale, torch.float32, "w_scale"),
+                                _dev(wq, torch.int8, "wq"), _dev(w_scale, torch.float32, "w_scale"), int(w_per_channel),
                                 _opt(bias, torch.float32, "bias"), _opt(residual, out_dtype, "residual"), int(relu),
                                 _dev(y, out_dtype, "y"), _dt(y), t, c_i, c_o, layout, wp, wb, _stream()),
            "sq_w8a8_linear")

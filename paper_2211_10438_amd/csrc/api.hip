@@ -52,7 +52,7 @@ size_t sq_workspace_bytes(sq_op op, int64_t t, int64_t c_i, int64_t c_o)
 {
     switch (op) {
         case SQ_OP_QUANTIZE_ACT: return 16;
-        case SQ_OP_PREPARE_WEIGHT: return 16;
+        case SQ_OP_PREPARE_WEIGHT: return 16 + (c_o > 0 ? (size_t)c_o * sizeof(uint32_t) : 0);  // column maxima (per-channel steps)
         case SQ_OP_W8A8_LINEAR:
         case SQ_OP_I8_GEMM_I32: return sq_gemm_workspace_bytes(t, c_i, c_o);
         case SQ_OP_W8A8_BMM: return 0;

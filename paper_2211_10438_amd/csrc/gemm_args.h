@@ -16,7 +16,8 @@ struct GemmArgs {
     void* C;  // [batch][M, N] 16-bit, row stride N
     const float* x_scale;  // [M] or [1] or NULL (then `alpha` is the whole scale)
     int per_token;
-    const float* w_scale;  // [1]
+    const float* w_scale;  // [1], or [N] with w_per_channel
+    int w_per_channel;
     float alpha;
     const float* bias;     // [N] or NULL
     const void* residual;  // [M, N] out dtype or NULL

@@ -404,7 +404,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
             }
             __syncthreads();
         }
-        const float ws = p.x_scale ? p.w_scale[0] : 0.0f;
+        const float ws = (p.x_scale && !p.w_per_channel) ? p.w_scale[0] : 0.0f;
         const float xs0 = (p.x_scale && !p.per_token) ? p.x_scale[0] : 0.0f;
         // The optional terms are compile-time flags inside the loop (one uniform switch outside) so the
         // common cases cost convert + multiply + round per element and one 8-byte LDS write per four.
@@ -414,14 +414,20 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
             for (int i = 0; i < MI; ++i) {
                 const int lrow = wm * WM + i * 32 + row_l;
                 const int row = m0 + lrow;
+                const float xrow = p.x_scale ? (p.per_token ? p.x_scale[row < p.M ? row : p.M - 1] : xs0) : 0.0f;
                 float c;
-                if (p.x_scale) c = (p.per_token ? p.x_scale[row < p.M ? row : p.M - 1] : xs0) * ws;
+                if (p.x_scale) c = xrow * ws;
                 else c = p.alpha;
 #pragma unroll
                 for (int j = 0; j < NI; ++j)
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         const int lcol = wn * WN + j * 32 + 8 * g + col_l;
+                        float cq[4] = {c, c, c, c};
+                        if (p.w_per_channel) {  // c = Delta_X[row] * Delta_W[col]
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) cq[e] = xrow * ((n0 + lcol + e < p.N) ? p.w_scale[n0 + lcol + e] : 0.0f);
+                        }
                         float bq[4] = {0.0f, 0.0f, 0.0f, 0.0f};
                         if constexpr (has_bias) {
 #pragma unroll
@@ -433,7 +439,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
                         uint32_t o[4];
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            o[e] = dequant_one<BF16>(acc[i][j][4 * g + e], c, bq[e], has_bias, relu, rb[e >> 1] >> ((e & 1) * 16),
+                            o[e] = dequant_one<BF16>(acc[i][j][4 * g + e], cq[e], bq[e], has_bias, relu, rb[e >> 1] >> ((e & 1) * 16),
                                                      has_res);
                         *slot = v2u{o[0] | (o[1] << 16), o[2] | (o[3] << 16)};
                     }
@@ -483,7 +489,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs p, in
             ((int32_t*)p.C)[idx] = sum;
         } else {
             float c;
-            if (p.x_scale) c = (p.per_token ? p.x_scale[row] : p.x_scale[0]) * p.w_scale[0];
+            if (p.x_scale) c = (p.per_token ? p.x_scale[row] : p.x_scale[0]) * p.w_scale[p.w_per_channel ? col : 0];
             else c = p.alpha;
             const uint16_t* R = (const uint16_t*)p.residual;
             ((uint16_t*)p.C)[idx] = (uint16_t)dequant_one<BF16>(sum, c, p.bias ? p.bias[col] : 0.0f, p.bias != nullptr,
@@ -668,7 +674,7 @@ size_t sq_gemm_workspace_bytes(int64_t t, int64_t c_i, int64_t c_o)
 }
 
 sq_status sq_w8a8_linear(const int8_t* xq, const float* x_scale, int x_scale_per_token, const int8_t* wq,
-                         const float* w_scale, const float* bias, const void* residual, int relu, void* y,
+                         const float* w_scale, int w_scale_per_channel, const float* bias, const void* residual, int relu, void* y,
                          sq_dtype out, int64_t t, int64_t c_i, int64_t c_o, sq_layout layout, void* workspace,
                          size_t ws_bytes, void* stream)
 {
@@ -685,6 +691,7 @@ sq_status sq_w8a8_linear(const int8_t* xq, const float* x_scale, int x_scale_per
     a.M = (int)t; a.N = (int)c_o; a.K = (int)c_i;
     a.lda = c_i; a.ldb = c_i;
     a.C = y; a.x_scale = x_scale; a.per_token = x_scale_per_token ? 1 : 0; a.w_scale = w_scale;
+    a.w_per_channel = w_scale_per_channel ? 1 : 0;
     a.bias = bias; a.residual = residual; a.relu = relu ? 1 : 0;
     return run_gemm(a, 1, false, out == SQ_BF16, workspace, ws_bytes, (hipStream_t)stream, false, layout == SQ_TILED);
 }

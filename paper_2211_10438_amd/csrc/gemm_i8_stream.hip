@@ -173,7 +173,7 @@ __global__ __launch_bounds__(NWAVE * 64, 1) void gemm_i8_stream_kernel(const Gem
     const int col_l = lane & 15, row_l = (lane >> 4) * 4;
     const bool raw = q.to_i32 || q.gk > 1;
     int32_t* out32 = p.acc_out + (int64_t)gki * p.M * p.N;
-    const float ws = (!raw && p.x_scale) ? p.w_scale[0] : 0.0f;
+    const float ws = (!raw && p.x_scale && !p.w_per_channel) ? p.w_scale[0] : 0.0f;
     const uint16_t* R = (const uint16_t*)p.residual;
 #pragma unroll
     for (int j = 0; j < NUW; ++j) {
@@ -182,6 +182,7 @@ __global__ __launch_bounds__(NWAVE * 64, 1) void gemm_i8_stream_kernel(const Gem
         const int col = (u0 + u) * 16 + col_l;
         if (col >= p.N) continue;
         const float bias = (!raw && p.bias) ? p.bias[col] : 0.0f;
+        const float wsc = (!raw && p.x_scale && p.w_per_channel) ? p.w_scale[col] : ws;
 #pragma unroll
         for (int i = 0; i < MB; ++i)
 #pragma unroll
@@ -193,7 +194,7 @@ __global__ __launch_bounds__(NWAVE * 64, 1) void gemm_i8_stream_kernel(const Gem
                     out32[idx] = acc[i][j][v];
                 } else {
                     float c;
-                    if (p.x_scale) c = (p.per_token ? p.x_scale[row] : p.x_scale[0]) * ws;
+                    if (p.x_scale) c = (p.per_token ? p.x_scale[row] : p.x_scale[0]) * wsc;
                     else c = p.alpha;
                     const uint32_t rb = R ? (uint32_t)R[idx] : 0u;
                     const uint32_t o = q.bf16 ? dequant_one<true>(acc[i][j][v], c, bias, p.bias != nullptr, p.relu != 0, rb, R != nullptr)

@@ -51,7 +51,32 @@ __global__ __launch_bounds__(256) void weight_row_absmax_kernel(const uint16_t* 
     }
 }
 
-__global__ void zero_u32_kernel(uint32_t* p) { if (threadIdx.x == 0) *p = 0u; }
+__global__ void zero_u32_kernel(uint32_t* p, int64_t n)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0u;
+}
+
+// Per-output-channel maxima: col_bits[n] = max_j |W_jn * s_j| as the bit pattern of a non-negative float
+// (its integer order is the float order, so atomicMax is exact).  A thread owns 8 neighbouring columns and
+// walks a slab of 64 rows; slabs are spread over blockIdx.y.
+template <bool BF16>
+__global__ __launch_bounds__(256) void weight_col_absmax_kernel(const uint16_t* __restrict__ w, int c_i, int c_o,
+                                                               const float* __restrict__ s, uint32_t* col_bits)
+{
+    const int n = (blockIdx.x * 256 + threadIdx.x) * 8;
+    if (n >= c_o) return;  // c_o % 8 == 0
+    const int j0 = blockIdx.y * 64, j1 = j0 + 64 < c_i ? j0 + 64 : c_i;
+    float m[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int j = j0; j < j1; ++j) {
+        float f[8];
+        unpack8w<BF16>(*(const v4u*)(w + (int64_t)j * c_o + n), f);
+        const float sj = s ? s[j] : 1.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) m[e] = __builtin_fmaxf(m[e], __builtin_fabsf(s ? f[e] * sj : f[e]));
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) atomicMax(col_bits + n + e, __builtin_bit_cast(uint32_t, m[e]));
+}
 
 // 64 (input channels) x 64 (output channels) tile: read along C_o, quantize, transpose through LDS,
 // write along C_i.
@@ -59,13 +84,18 @@ template <bool BF16>
 __global__ __launch_bounds__(256) void weight_quant_transpose_kernel(const uint16_t* __restrict__ w, int c_i, int c_o,
                                                                     const float* __restrict__ s,
                                                                     const uint32_t* amax_bits, float* w_scale,
-                                                                    int8_t* __restrict__ wq, bool tiled)
+                                                                    int8_t* __restrict__ wq, bool tiled, bool per_channel)
 {
     __shared__ __attribute__((aligned(16))) int8_t tileT[64][80];  // [n][j], padded pitch
-    const float a = __builtin_bit_cast(float, *amax_bits);
+    const float a = __builtin_bit_cast(float, *amax_bits);  // per-tensor maximum (per_channel: unused)
     const float r = a > 0.0f ? 127.0f / a : 0.0f;
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) w_scale[0] = a / 127.0f;
     const int j0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+    if (per_channel) {  // amax_bits[n]: maximum of column n
+        if (blockIdx.y == 0 && threadIdx.x < 64 && n0 + threadIdx.x < c_o)
+            w_scale[n0 + threadIdx.x] = __builtin_bit_cast(float, amax_bits[n0 + threadIdx.x]) / 127.0f;
+    } else if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+        w_scale[0] = a / 127.0f;
+    }
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int v = threadIdx.x + h * 256;  // 512 vectors: 64 rows x 8 vectors of 8 channels
@@ -76,7 +106,14 @@ __global__ __launch_bounds__(256) void weight_quant_transpose_kernel(const uint1
             unpack8w<BF16>(*(const v4u*)(w + (int64_t)j * c_o + n), f);
             const float sj = s ? s[j] : 1.0f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) tileT[nl + e][jl] = (int8_t)round_code((s ? f[e] * sj : f[e]) * r);
+            for (int e = 0; e < 8; ++e) {
+                float re = r;
+                if (per_channel) {
+                    const float an = __builtin_bit_cast(float, amax_bits[n + e]);
+                    re = an > 0.0f ? 127.0f / an : 0.0f;
+                }
+                tileT[nl + e][jl] = (int8_t)round_code((s ? f[e] * sj : f[e]) * re);
+            }
         }
     }
     __syncthreads();
@@ -108,7 +145,8 @@ sq_status sq_weight_absmax_per_in_channel(const void* w, sq_dtype dtype, int64_t
 }
 
 sq_status sq_prepare_weight(const void* w, sq_dtype dtype, const float* s, int64_t c_i, int64_t c_o, int8_t* wq,
-                            sq_layout wq_layout, float* w_scale, void* workspace, size_t ws_bytes, void* stream)
+                            sq_layout wq_layout, float* w_scale, int w_scale_per_channel, void* workspace, size_t ws_bytes,
+                            void* stream)
 {
     if (!w || !wq || !w_scale) return SQ_ERR_NULL;
     if (c_i <= 0 || c_o <= 0 || c_i >= ((int64_t)1 << 31) || c_o >= ((int64_t)1 << 31)) return SQ_ERR_SHAPE;
@@ -117,18 +155,24 @@ sq_status sq_prepare_weight(const void* w, sq_dtype dtype, const float* s, int64
     if ((c_i & 15) || (c_o & 7) || !sq_aligned16(w) || !sq_aligned16(wq)) return SQ_ERR_ALIGN;
     if (wq_layout == SQ_TILED && (c_i & 63)) return SQ_ERR_ALIGN;
     const bool tiled = wq_layout == SQ_TILED;
-    if (!workspace || ws_bytes < sizeof(uint32_t)) return SQ_ERR_WORKSPACE;
+    const bool pc = w_scale_per_channel != 0;
+    if (!workspace || ws_bytes < sizeof(uint32_t) * (pc ? (size_t)c_o : 1)) return SQ_ERR_WORKSPACE;
+    if (((int64_t)((c_i + 63) / 64)) > 65535) return SQ_ERR_SHAPE;
     hipStream_t st = (hipStream_t)stream;
     uint32_t* amax = (uint32_t*)workspace;
-    hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(64), 0, st, amax);
+    const int64_t ncell = pc ? c_o : 1;
+    hipLaunchKernelGGL(zero_u32_kernel, dim3((unsigned)((ncell + 255) / 256 < 1024 ? (ncell + 255) / 256 : 1024)), dim3(256), 0, st, amax, ncell);
     const unsigned grid1 = (unsigned)(c_i < 4096 ? c_i : 4096);
+    dim3 gridc((unsigned)((c_o / 8 + 255) / 256), (unsigned)((c_i + 63) / 64));
     dim3 grid2((unsigned)((c_o + 63) / 64), (unsigned)((c_i + 63) / 64));
     if (dtype == SQ_BF16) {
-        hipLaunchKernelGGL(weight_row_absmax_kernel<true>, dim3(grid1), dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, (float*)nullptr, amax);
-        hipLaunchKernelGGL(weight_quant_transpose_kernel<true>, grid2, dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, amax, w_scale, wq, tiled);
+        if (pc) hipLaunchKernelGGL(weight_col_absmax_kernel<true>, gridc, dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, amax);
+        else hipLaunchKernelGGL(weight_row_absmax_kernel<true>, dim3(grid1), dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, (float*)nullptr, amax);
+        hipLaunchKernelGGL(weight_quant_transpose_kernel<true>, grid2, dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, amax, w_scale, wq, tiled, pc);
     } else {
-        hipLaunchKernelGGL(weight_row_absmax_kernel<false>, dim3(grid1), dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, (float*)nullptr, amax);
-        hipLaunchKernelGGL(weight_quant_transpose_kernel<false>, grid2, dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, amax, w_scale, wq, tiled);
+        if (pc) hipLaunchKernelGGL(weight_col_absmax_kernel<false>, gridc, dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, amax);
+        else hipLaunchKernelGGL(weight_row_absmax_kernel<false>, dim3(grid1), dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, (float*)nullptr, amax);
+        hipLaunchKernelGGL(weight_quant_transpose_kernel<false>, grid2, dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, amax, w_scale, wq, tiled, pc);
     }
     return sq_launch_status();
 }

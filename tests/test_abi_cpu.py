@@ -66,15 +66,15 @@ def test_argument_validation_happens_before_any_launch():
     assert L.sq_quantize_act(fake, 0, 4, 64, 64, NULL, 9, fake, fake, 0, NULL, 0, NULL) == 4   # mode
     assert L.sq_quantize_act(fake, 0, 4, 64, 64, NULL, 1, fake, fake, 0, NULL, 0, NULL) == 5   # O2 needs workspace
     # linear
-    assert L.sq_w8a8_linear(NULL, fake, 1, fake, fake, NULL, NULL, 0, fake, 0, 4, 64, 64, 0, NULL, 0, NULL) == 1
-    assert L.sq_w8a8_linear(fake, fake, 1, fake, fake, NULL, NULL, 0, fake, 0, 4, 0, 64, 0, NULL, 0, NULL) == 2
-    assert L.sq_w8a8_linear(fake, fake, 1, fake, fake, NULL, NULL, 0, fake, 0, 4, 40, 64, 0, NULL, 0, NULL) == 3
-    assert L.sq_w8a8_linear(fake, fake, 1, fake, fake, NULL, NULL, 0, fake, 0, 4, 80, 64, 1, NULL, 0, NULL) == 3  # tiled: c_i % 64
-    assert L.sq_w8a8_linear(fake, fake, 1, fake, fake, NULL, NULL, 0, fake, 5, 4, 64, 64, 0, NULL, 0, NULL) == 4
+    assert L.sq_w8a8_linear(NULL, fake, 1, fake, fake, 0, NULL, NULL, 0, fake, 0, 4, 64, 64, 0, NULL, 0, NULL) == 1
+    assert L.sq_w8a8_linear(fake, fake, 1, fake, fake, 0, NULL, NULL, 0, fake, 0, 4, 0, 64, 0, NULL, 0, NULL) == 2
+    assert L.sq_w8a8_linear(fake, fake, 1, fake, fake, 0, NULL, NULL, 0, fake, 0, 4, 40, 64, 0, NULL, 0, NULL) == 3
+    assert L.sq_w8a8_linear(fake, fake, 1, fake, fake, 0, NULL, NULL, 0, fake, 0, 4, 80, 64, 1, NULL, 0, NULL) == 3  # tiled: c_i % 64
+    assert L.sq_w8a8_linear(fake, fake, 1, fake, fake, 0, NULL, NULL, 0, fake, 5, 4, 64, 64, 0, NULL, 0, NULL) == 4
     # a split-K shape (few tokens, long K, narrow C_o) without workspace
     need = L.sq_workspace_bytes(sq.OP_W8A8_LINEAR, 16, 12288, 1536)
     assert need > 0
-    assert L.sq_w8a8_linear(fake, fake, 1, fake, fake, NULL, NULL, 0, fake, 0, 16, 12288, 1536, 0, NULL, 0, NULL) == 5
+    assert L.sq_w8a8_linear(fake, fake, 1, fake, fake, 0, NULL, NULL, 0, fake, 0, 16, 12288, 1536, 0, NULL, 0, NULL) == 5
     # few tokens against a wide C_o stream W in one pass: no workspace
     assert L.sq_workspace_bytes(sq.OP_W8A8_LINEAR, 16, 12288, 12288) == 0
     assert L.sq_i8_gemm_i32(fake, NULL, fake, 4, 64, 64, 0, NULL, 0, NULL) == 1
@@ -83,8 +83,10 @@ def test_argument_validation_happens_before_any_launch():
     assert L.sq_w8a8_bmm(fake, fake, 1, 1.0, fake, 0, 2, 16, 16, 24, 384, 384, 256, NULL) == 3
     assert L.sq_w8a8_bmm(fake, fake, 1, 1.0, fake, 0, 2, 16, 16, 16, 100, 256, 256, NULL) == 2  # stride < m*k
     # weight prep / rowops
-    assert L.sq_prepare_weight(fake, 0, NULL, 64, 64, fake, 0, fake, NULL, 0, NULL) == 5
-    assert L.sq_prepare_weight(fake, 0, NULL, 60, 64, fake, 0, fake, fake, 16, NULL) == 3
+    assert L.sq_prepare_weight(fake, 0, NULL, 64, 64, fake, 0, fake, 0, NULL, 0, NULL) == 5
+    assert L.sq_prepare_weight(fake, 0, NULL, 60, 64, fake, 0, fake, 0, fake, 16, NULL) == 3
+    assert L.sq_prepare_weight(fake, 0, NULL, 64, 64, fake, 0, fake, 1, fake, 16, NULL) == 5   # per-channel: 4 * c_o bytes
+    assert L.sq_workspace_bytes(sq.OP_PREPARE_WEIGHT, 0, 64, 64) >= 4 * 64
     assert L.sq_softmax_quant_p(fake, 0, 4, 20, fake, NULL) == 3
     assert L.sq_ln_quantize(fake, 0, 4, 64, NULL, fake, 1e-5, fake, fake, 0, NULL) == 1
     assert L.sq_tiled_bytes(33, 128) == 48 * 128 and L.sq_tiled_bytes(33, 100) == 0
