@@ -132,6 +132,20 @@ sq_status sq_w8a8_linear(const int8_t* xq, const float* x_scale, int x_scale_per
                          int64_t c_i, int64_t c_o, sq_layout layout, void* workspace, size_t ws_bytes,
                          void* stream);
 
+/* The same layer with the static activation quantizer of the NEXT int8 kernel fused into the epilogue (the
+ * "fuse into the previous layer" idea of Sec. 4 applied to the quantize step; Table 2's O3 pipeline):
+ *   v16 = the 16-bit value sq_w8a8_linear would store, in dtype `mid`;
+ *   yq_tn = clamp(round_half_even(fl32(v16 * fl32(1 / y_step))), -127, 127)   -- sq_quantize_act, static mode.
+ * So the codes equal sq_quantize_act(SQ_PER_TENSOR_STATIC) applied to sq_w8a8_linear's output, without the
+ * 16-bit tensor ever reaching HBM.  y_step: device fp32 [1], the calibrated Delta of the output tensor;
+ * yq: device int8 [t, c_o] in `yq_layout` (SQ_TILED: c_o % 64 == 0, sq_tiled_bytes(t, c_o) bytes); c_o % 8 == 0;
+ * residual: of dtype `mid`.  Other arguments as sq_w8a8_linear. */
+sq_status sq_w8a8_linear_q8(const int8_t* xq, const float* x_scale, int x_scale_per_token,
+                            const int8_t* wq, const float* w_scale, int w_scale_per_channel,
+                            const float* bias, const void* residual, int relu, sq_dtype mid,
+                            const float* y_step, int8_t* yq, sq_layout yq_layout, int64_t t, int64_t c_i,
+                            int64_t c_o, sq_layout layout, void* workspace, size_t ws_bytes, void* stream);
+
 /* The raw integer contraction of Eq. 2 (test export: makes the bit-exact int32 gate observable).
  * acc: device int32 [t, c_o] row-major; layout: layout of both xq and wq. */
 sq_status sq_i8_gemm_i32(const int8_t* xq, const int8_t* wq, int32_t* acc, int64_t t, int64_t c_i,

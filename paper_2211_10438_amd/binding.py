@@ -22,7 +22,7 @@ ROW_MAJOR, TILED = 0, 1
 
 EXPORTS = (
     "sq_status_string", "sq_smooth_scales", "sq_act_absmax_per_channel", "sq_weight_absmax_per_in_channel",
-    "sq_prepare_weight", "sq_quantize_act", "sq_w8a8_linear", "sq_i8_gemm_i32", "sq_w8a8_bmm",
+    "sq_prepare_weight", "sq_quantize_act", "sq_w8a8_linear", "sq_w8a8_linear_q8", "sq_i8_gemm_i32", "sq_w8a8_bmm",
     "sq_softmax_quant_p", "sq_ln_quantize", "sq_workspace_bytes", "sq_tiled_bytes",
 )
 
@@ -51,6 +51,8 @@ def lib() -> ctypes.CDLL:
         L.sq_prepare_weight.argtypes = [vp, i32, vp, i64, i64, vp, i32, vp, i32, vp, ctypes.c_size_t, vp]
         L.sq_quantize_act.argtypes = [vp, i32, i64, i64, i64, vp, i32, vp, vp, i32, vp, ctypes.c_size_t, vp]
         L.sq_w8a8_linear.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, i32, vp, i32, i64, i64, i64, i32, vp, ctypes.c_size_t, vp]
+        L.sq_w8a8_linear_q8.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, i32, i32, vp, vp, i32, i64, i64, i64, i32, vp,
+                                        ctypes.c_size_t, vp]
         L.sq_i8_gemm_i32.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, ctypes.c_size_t, vp]
         L.sq_w8a8_bmm.argtypes = [vp, vp, i32, f32, vp, i32, i64, i64, i64, i64, i64, i64, i64, vp]
         L.sq_softmax_quant_p.argtypes = [vp, i32, i64, i64, vp, vp]
@@ -220,6 +222,27 @@ def w8a8_linear(xq: torch.Tensor, x_scale: torch.Tensor, wq: torch.Tensor, w_sca
                                 _dev(y, out_dtype, "y"), _dt(y), t, c_i, c_o, layout, wp, wb, _stream()),
            "sq_w8a8_linear")
     return y
+
+
+def w8a8_linear_q8(xq: torch.Tensor, x_scale: torch.Tensor, wq: torch.Tensor, w_scale: torch.Tensor, y_step: torch.Tensor,
+                   mid_dtype, bias=None, residual=None, relu: bool = False, out=None, workspace=None,
+                   layout: int = ROW_MAJOR, out_layout: int = ROW_MAJOR, w_per_channel: bool | None = None) -> torch.Tensor:
+    """W8A8 linear whose epilogue also applies the static quantizer of the next int8 kernel: returns int8 codes
+    [t, c_o] (in ``out_layout``) of the value rounded to ``mid_dtype``, with the calibrated step ``y_step`` [1]."""
+    t, c_i = xq.shape
+    c_o = wq.shape[0]
+    if w_per_channel is None:
+        w_per_channel = w_scale.numel() == c_o and c_o > 1
+    yq = empty_codes(t, c_o, out_layout, xq.device) if out is None else out
+    wp, wb, keep = _workspace(workspace_bytes(OP_W8A8_LINEAR, t, c_i, c_o), xq.device, workspace)
+    mid = F16 if mid_dtype == torch.float16 else BF16
+    _check(lib().sq_w8a8_linear_q8(_dev(xq, torch.int8, "xq"), _dev(x_scale, torch.float32, "x_scale"),
+                                   int(x_scale.numel() == t), _dev(wq, torch.int8, "wq"),
+                                   _dev(w_scale, torch.float32, "w_scale"), int(w_per_channel),
+                                   _opt(bias, torch.float32, "bias"), _opt(residual, mid_dtype, "residual"), int(relu), mid,
+                                   _dev(y_step, torch.float32, "y_step"), yq.data_ptr(), out_layout, t, c_i, c_o, layout,
+                                   wp, wb, _stream()), "sq_w8a8_linear_q8")
+    return yq
 
 
 def i8_gemm_i32(xq: torch.Tensor, wq: torch.Tensor, workspace=None, layout: int = ROW_MAJOR) -> torch.Tensor:

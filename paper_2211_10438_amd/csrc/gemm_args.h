@@ -24,7 +24,19 @@ struct GemmArgs {
     int relu;
     // int32 output (raw accumulators or split-K partials): [splits][M, N]
     int32_t* acc_out;
+    // int8 output (producer-side fusion): when q8_step is set, the 16-bit value the epilogue would have stored is
+    // quantized with the calibrated step q8_step[0] (Eq. 1, static) and written to q8_out [M, N] instead of C.
+    const float* q8_step;
+    int8_t* q8_out;
+    int q8_tiled;
 };
+
+// Static per-tensor quantization of a value that has already been rounded to the 16-bit type `BF16` selects:
+// the same arithmetic as the static mode of the activation quantizer (x * fl32(1 / Delta), nearest-even, +-127).
+template <bool BF16> SQ_DEVICE int requant_code(uint32_t bits16, float r)
+{
+    return round_code(load16_bits<BF16>(bits16) * r);
+}
 
 template <int N> SQ_DEVICE void wait_vmcnt_imm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 

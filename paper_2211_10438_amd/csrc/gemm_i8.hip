@@ -458,11 +458,33 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
             default: phase1(T_{}, T_{}, T_{}); break;
         }
         __syncthreads();
+        float rq = 0.0f;
+        if (p.q8_step) {
+            const float delta = p.q8_step[0];
+            rq = delta > 0.0f ? 1.0f / delta : 0.0f;
+        }
         for (int q = threadIdx.x; q < BM * CPR; q += NW * 64) {
             const int r = q / CPR, c8 = (q - r * CPR) * 8;
             const int row = m0 + r, col = n0 + c8;
             if (row < p.M && col < p.N) {
                 const v4u val = *(const v4u*)(smem + r * PITCH + c8 * 2);
+                if (p.q8_step) {
+                    // int8 output: quantize the eight 16-bit values of this chunk (they never straddle a
+                    // 16-byte chunk of the tiled layout) and store 8 codes
+                    int cq[8];
+#pragma unroll
+                    for (int t = 0; t < 8; ++t) cq[t] = requant_code<BF16>(val[t >> 1] >> ((t & 1) * 16), rq);
+                    int8_t* dq = code_dst(p.q8_out, row, col, p.N, p.q8_tiled != 0);
+                    if (vec_ok) {
+                        *(v2u*)dq = v2u{(uint32_t)(cq[0] & 0xff) | ((uint32_t)(cq[1] & 0xff) << 8) | ((uint32_t)(cq[2] & 0xff) << 16) | ((uint32_t)(cq[3] & 0xff) << 24),
+                                        (uint32_t)(cq[4] & 0xff) | ((uint32_t)(cq[5] & 0xff) << 8) | ((uint32_t)(cq[6] & 0xff) << 16) | ((uint32_t)(cq[7] & 0xff) << 24)};
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < 8; ++t)
+                            if (col + t < p.N) dq[t] = (int8_t)cq[t];
+                    }
+                    continue;
+                }
                 uint16_t* dst = C + (int64_t)row * p.N + col;
                 if (vec_ok) {
                     __builtin_nontemporal_store(val, (v4u*)dst);
@@ -492,8 +514,15 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmArgs p, in
             if (p.x_scale) c = (p.per_token ? p.x_scale[row] : p.x_scale[0]) * p.w_scale[p.w_per_channel ? col : 0];
             else c = p.alpha;
             const uint16_t* R = (const uint16_t*)p.residual;
-            ((uint16_t*)p.C)[idx] = (uint16_t)dequant_one<BF16>(sum, c, p.bias ? p.bias[col] : 0.0f, p.bias != nullptr,
-                                                                p.relu != 0, R ? R[idx] : 0u, R != nullptr);
+            const uint32_t o = dequant_one<BF16>(sum, c, p.bias ? p.bias[col] : 0.0f, p.bias != nullptr, p.relu != 0,
+                                                 R ? R[idx] : 0u, R != nullptr);
+            if (p.q8_step) {
+                const float delta = p.q8_step[0];
+                code_dst(p.q8_out, row, col & ~7, p.N, p.q8_tiled != 0)[col & 7] =
+                    (int8_t)requant_code<BF16>(o, delta > 0.0f ? 1.0f / delta : 0.0f);
+            } else {
+                ((uint16_t*)p.C)[idx] = (uint16_t)o;
+            }
         }
     }
 }
@@ -694,6 +723,33 @@ sq_status sq_w8a8_linear(const int8_t* xq, const float* x_scale, int x_scale_per
     a.w_per_channel = w_scale_per_channel ? 1 : 0;
     a.bias = bias; a.residual = residual; a.relu = relu ? 1 : 0;
     return run_gemm(a, 1, false, out == SQ_BF16, workspace, ws_bytes, (hipStream_t)stream, false, layout == SQ_TILED);
+}
+
+sq_status sq_w8a8_linear_q8(const int8_t* xq, const float* x_scale, int x_scale_per_token, const int8_t* wq,
+                            const float* w_scale, int w_scale_per_channel, const float* bias, const void* residual,
+                            int relu, sq_dtype mid, const float* y_step, int8_t* yq, sq_layout yq_layout, int64_t t,
+                            int64_t c_i, int64_t c_o, sq_layout layout, void* workspace, size_t ws_bytes, void* stream)
+{
+    if (!xq || !x_scale || !wq || !w_scale || !y_step || !yq) return SQ_ERR_NULL;
+    if (!dims_ok(t, c_i, c_o)) return SQ_ERR_SHAPE;
+    if (mid != SQ_F16 && mid != SQ_BF16) return SQ_ERR_UNSUPPORTED;
+    if (layout != SQ_ROW_MAJOR && layout != SQ_TILED) return SQ_ERR_UNSUPPORTED;
+    if (yq_layout != SQ_ROW_MAJOR && yq_layout != SQ_TILED) return SQ_ERR_UNSUPPORTED;
+    if (layout == SQ_TILED && (c_i & 63)) return SQ_ERR_ALIGN;
+    if (yq_layout == SQ_TILED && (c_o & 63)) return SQ_ERR_ALIGN;
+    if ((c_i & 15) || (c_o & 7) || !sq_aligned16(xq) || !sq_aligned16(wq) || !sq_aligned16(yq) ||
+        (residual && !sq_aligned16(residual)) || (workspace && !sq_aligned16(workspace)))
+        return SQ_ERR_ALIGN;
+    GemmArgs a{};
+    a.A = xq; a.B = wq;
+    a.M = (int)t; a.N = (int)c_o; a.K = (int)c_i;
+    a.lda = c_i; a.ldb = c_i;
+    a.C = yq;  // never written: the epilogues branch on q8_step
+    a.x_scale = x_scale; a.per_token = x_scale_per_token ? 1 : 0; a.w_scale = w_scale;
+    a.w_per_channel = w_scale_per_channel ? 1 : 0;
+    a.bias = bias; a.residual = residual; a.relu = relu ? 1 : 0;
+    a.q8_step = y_step; a.q8_out = yq; a.q8_tiled = yq_layout == SQ_TILED ? 1 : 0;
+    return run_gemm(a, 1, false, mid == SQ_BF16, workspace, ws_bytes, (hipStream_t)stream, false, layout == SQ_TILED);
 }
 
 sq_status sq_i8_gemm_i32(const int8_t* xq, const int8_t* wq, int32_t* acc, int64_t t, int64_t c_i, int64_t c_o,

@@ -175,6 +175,11 @@ __global__ __launch_bounds__(NWAVE * 64, 1) void gemm_i8_stream_kernel(const Gem
     int32_t* out32 = p.acc_out + (int64_t)gki * p.M * p.N;
     const float ws = (!raw && p.x_scale && !p.w_per_channel) ? p.w_scale[0] : 0.0f;
     const uint16_t* R = (const uint16_t*)p.residual;
+    float rq = 0.0f;
+    if (!raw && p.q8_step) {
+        const float delta = p.q8_step[0];
+        rq = delta > 0.0f ? 1.0f / delta : 0.0f;
+    }
 #pragma unroll
     for (int j = 0; j < NUW; ++j) {
         const int u = j * WN + wn;
@@ -199,7 +204,12 @@ __global__ __launch_bounds__(NWAVE * 64, 1) void gemm_i8_stream_kernel(const Gem
                     const uint32_t rb = R ? (uint32_t)R[idx] : 0u;
                     const uint32_t o = q.bf16 ? dequant_one<true>(acc[i][j][v], c, bias, p.bias != nullptr, p.relu != 0, rb, R != nullptr)
                                               : dequant_one<false>(acc[i][j][v], c, bias, p.bias != nullptr, p.relu != 0, rb, R != nullptr);
-                    ((uint16_t*)p.C)[idx] = (uint16_t)o;
+                    if (p.q8_step) {
+                        const int code = q.bf16 ? requant_code<true>(o, rq) : requant_code<false>(o, rq);
+                        code_dst(p.q8_out, row, col & ~7, p.N, p.q8_tiled != 0)[col & 7] = (int8_t)code;
+                    } else {
+                        ((uint16_t*)p.C)[idx] = (uint16_t)o;
+                    }
                 }
             }
     }

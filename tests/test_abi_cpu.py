@@ -78,6 +78,11 @@ def test_argument_validation_happens_before_any_launch():
     # few tokens against a wide C_o stream W in one pass: no workspace
     assert L.sq_workspace_bytes(sq.OP_W8A8_LINEAR, 16, 12288, 12288) == 0
     assert L.sq_i8_gemm_i32(fake, NULL, fake, 4, 64, 64, 0, NULL, 0, NULL) == 1
+    # linear with int8 output
+    assert L.sq_w8a8_linear_q8(fake, fake, 1, fake, fake, 0, NULL, NULL, 0, 0, NULL, fake, 0, 4, 64, 64, 0, NULL, 0, NULL) == 1  # y_step
+    assert L.sq_w8a8_linear_q8(fake, fake, 1, fake, fake, 0, NULL, NULL, 0, 0, fake, fake, 1, 4, 64, 72, 0, NULL, 0, NULL) == 3  # tiled out: c_o % 64
+    assert L.sq_w8a8_linear_q8(fake, fake, 1, fake, fake, 0, NULL, NULL, 0, 0, fake, fake, 0, 4, 64, 60, 0, NULL, 0, NULL) == 3  # c_o % 8
+    assert L.sq_w8a8_linear_q8(fake, fake, 1, fake, fake, 0, NULL, NULL, 0, 3, fake, fake, 0, 4, 64, 64, 0, NULL, 0, NULL) == 4  # mid dtype
     # bmm
     assert L.sq_w8a8_bmm(fake, fake, 1, 1.0, fake, 0, 0, 16, 16, 16, 256, 256, 256, NULL) == 2
     assert L.sq_w8a8_bmm(fake, fake, 1, 1.0, fake, 0, 2, 16, 16, 24, 384, 384, 256, NULL) == 3
