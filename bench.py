@@ -62,6 +62,82 @@ def run_layer(sq, torch, L):
     sq.w8a8_linear(L["xq"], L["x_scale"], L["wq"], L["w_scale"], torch.bfloat16, out=L["y"], workspace=L["ws"], layout=sq.TILED)
 
 
+def _time_us(torch, fn, iters=10, warm=2):
+    for _ in range(warm):
+        fn()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(iters):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / iters * 1e3
+
+
+def other_configs(sq, torch):
+    """Latency and roofline fraction of the other benchmark configurations (synthetic inputs of their shapes):
+    1 = OPT-125m-shaped static linear, 2 = OPT-13B-shaped FFN pair, 4 = INT8 attention BMMs (batch 8 x 96 heads,
+    sequence 2048, head_dim 128), 5 = the linears and attention of an OPT-66B-shaped decoder layer (4 x 1024 tokens)."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(77)
+    out = {}
+
+    def rand16(shape, scale=1.0):
+        return (torch.randn(shape, generator=g, device="cuda") * scale).to(torch.float16)
+
+    def linear_pair(t, c_i, c_o, relu=False, static=False):
+        x = rand16((t, c_i))
+        wq, ws = sq.prepare_weight(rand16((c_i, c_o), 0.02), None, layout=sq.TILED)
+        xq = sq.empty_codes(t, c_i, sq.TILED)
+        xs = torch.empty(1 if static else t, dtype=torch.float32, device="cuda")
+        if static:
+            xs.fill_(float(x.abs().max()) / 127.0)
+        y = torch.empty((t, c_o), dtype=torch.float16, device="cuda")
+        wsp = torch.empty(max(sq.workspace_bytes(sq.OP_W8A8_LINEAR, t, c_i, c_o), 16), dtype=torch.uint8, device="cuda")
+        mode = sq.PER_TENSOR_STATIC if static else sq.PER_TOKEN_DYNAMIC
+        q_us = _time_us(torch, lambda: sq.quantize_act(x, mode, static_scale=xs if static else None, out=(xq, xs), layout=sq.TILED))
+        g_us = _time_us(torch, lambda: sq.w8a8_linear(xq, xs, wq, ws, torch.float16, relu=relu, out=y, workspace=wsp, layout=sq.TILED))
+        ops = 2.0 * t * c_i * c_o
+        return {"quantize_us": round(q_us, 1), "gemm_us": round(g_us, 1), "tops": round(ops / (q_us + g_us) / 1e6, 1),
+                "frac_mfma_peak": round(ops / (q_us + g_us) / 1e6 / PEAK_INT8_TOPS, 4)}
+
+    out["config1_opt125m_static_16x768x3072"] = linear_pair(16, 768, 3072, static=True)
+    out["config2_opt13b_fc1_512x5120x20480_relu"] = linear_pair(512, 5120, 20480, relu=True)
+    out["config2_opt13b_fc2_512x20480x5120"] = linear_pair(512, 20480, 5120)
+
+    def attention(bh, s_len, d):
+        q, k, v = (torch.randint(-127, 128, (bh, s_len, d), dtype=torch.int8, device="cuda", generator=g) for _ in range(3))
+        sc = torch.empty((bh, s_len, s_len), dtype=torch.float16, device="cuda")
+        pq = torch.empty((bh, s_len, s_len), dtype=torch.int8, device="cuda")
+        o = torch.empty((bh, s_len, d), dtype=torch.float16, device="cuda")
+        t1 = _time_us(torch, lambda: sq.w8a8_bmm(q, k, True, 2e-5, torch.float16, out=sc), iters=5, warm=1)
+        t2 = _time_us(torch, lambda: sq.softmax_quant_p(sc, out=pq), iters=5, warm=1)
+        t3 = _time_us(torch, lambda: sq.w8a8_bmm(pq, v, False, 1e-4, torch.float16, out=o), iters=5, warm=1)
+        b1 = 2.0 * bh * s_len * d + 2.0 * bh * s_len * s_len
+        b2 = 3.0 * bh * s_len * s_len
+        b3 = bh * s_len * s_len + 3.0 * bh * s_len * d
+        return {"bmm1_us": round(t1, 1), "bmm1_frac_hbm": round(b1 / t1 / 1e3 / PEAK_HBM_GBS, 4),
+                "softmax_quant_us": round(t2, 1), "softmax_frac_hbm": round(b2 / t2 / 1e3 / PEAK_HBM_GBS, 4),
+                "bmm2_us": round(t3, 1), "bmm2_frac_hbm": round(b3 / t3 / 1e3 / PEAK_HBM_GBS, 4),
+                "tops_both_bmms": round(4.0 * bh * s_len * s_len * d / (t1 + t3) / 1e6, 1)}
+
+    out["config4_attention_768x2048x128"] = attention(768, 2048, 128)
+    out["config5_opt66b_qkv_4096x9216x27648"] = linear_pair(4096, 9216, 27648)
+    out["config5_opt66b_out_proj_4096x9216x9216"] = linear_pair(4096, 9216, 9216)
+    out["config5_opt66b_fc1_4096x9216x36864_relu"] = linear_pair(4096, 9216, 36864, relu=True)
+    out["config5_opt66b_fc2_4096x36864x9216"] = linear_pair(4096, 36864, 9216)
+    out["config5_attention_288x1024x128"] = attention(288, 1024, 128)
+    x = rand16((4096, 9216))
+    gamma = torch.ones(9216, device="cuda")
+    beta = torch.zeros(9216, device="cuda")
+    xq = sq.empty_codes(4096, 9216, sq.TILED)
+    xs = torch.empty(4096, dtype=torch.float32, device="cuda")
+    ln_us = _time_us(torch, lambda: sq.ln_quantize(x, gamma, beta, out=(xq, xs), layout=sq.TILED))
+    out["config5_ln_quantize_4096x9216"] = {"us": round(ln_us, 1),
+                                            "frac_hbm": round(3.0 * 4096 * 9216 / ln_us / 1e3 / PEAK_HBM_GBS, 4)}
+    return out
+
+
 def cpu_baseline(layers_desc):
     """The oracle as it stands, timed on the host cores on a bounded sample of the same workload:
     every layer at the full 2048 tokens (quantize + linear with epilogue), about 10-20 s of CPU work."""
@@ -234,6 +310,9 @@ def main():
     out["decode"] = {"bound": "hbm", "peak_GBs": PEAK_HBM_GBS,
                      "note": "same four layers, quantize + linear per layer, bytes = int8 W + fp16 x in + codes out/in + "
                              "bf16 y out; weights stream from HBM on every pass (1.8 GB per pass)", **decode}
+    layers.clear()
+    torch.cuda.empty_cache()
+    out["other_configs"] = other_configs(sq, torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(desc)
     print(json.dumps(out))

@@ -41,6 +41,20 @@ SQ_DEVICE int round_code(float v)
     return (int)r;
 }
 
+// The same rounding with the code left in the low byte of a word (two's complement), three instructions:
+// clamp to +-127 (v_med3_f32; clamping before or after rounding gives the same integer), then add 1.5 * 2^23:
+// the adder's own round-to-nearest-even leaves the integer in the low mantissa bits.
+SQ_DEVICE uint32_t code_bits(float v)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_fmed3f(v, -127.0f, 127.0f) + 12582912.0f);
+}
+// Low bytes of four words -> one word (byte e from word e), three v_perm_b32.
+SQ_DEVICE uint32_t pack4_low_bytes(uint32_t b0, uint32_t b1, uint32_t b2, uint32_t b3)
+{
+    const uint32_t lo = __builtin_amdgcn_perm(b1, b0, 0x0c0c0400u), hi = __builtin_amdgcn_perm(b3, b2, 0x0c0c0400u);
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+}
+
 // Byte offset of element (r, c) of an int8 [rows, k] operand in the SQ_TILED layout (see sqmi.h).
 SQ_DEVICE int64_t tiled_offset(int64_t r, int c, int k)
 {

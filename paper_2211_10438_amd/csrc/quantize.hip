@@ -41,12 +41,9 @@ SQ_DEVICE v2u quant8(const float (&f)[8], float r)
 {
     v2u out;
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        uint32_t w = 0;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) w |= ((uint32_t)round_code(f[4 * h + e] * r) & 0xffu) << (8 * e);
-        out[h] = w;
-    }
+    for (int h = 0; h < 2; ++h)
+        out[h] = pack4_low_bytes(code_bits(f[4 * h] * r), code_bits(f[4 * h + 1] * r), code_bits(f[4 * h + 2] * r),
+                                 code_bits(f[4 * h + 3] * r));
     return out;
 }
 

@@ -22,29 +22,33 @@ template <bool BF16> SQ_DEVICE void unpack8r(const v4u raw, float (&f)[8])
 // made this pass ALU-bound.
 SQ_DEVICE float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896340736f); }
 
-SQ_DEVICE float block_max_r(float v, float* red)
+template <int NT = 256> SQ_DEVICE float block_max_r(float v, float* red)
 {
     v = wave_max(v);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
     __syncthreads();
-    return __builtin_fmaxf(__builtin_fmaxf(red[0], red[1]), __builtin_fmaxf(red[2], red[3]));
+    float m = __builtin_fmaxf(__builtin_fmaxf(red[0], red[1]), __builtin_fmaxf(red[2], red[3]));
+#pragma unroll
+    for (int w = 4; w < NT / 64; w += 4)
+        m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fmaxf(red[w], red[w + 1]), __builtin_fmaxf(red[w + 2], red[w + 3])));
+    return m;
 }
-SQ_DEVICE float block_sum_r(float v, float* red)
+template <int NT = 256> SQ_DEVICE float block_sum_r(float v, float* red)
 {
     v = wave_sum(v);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
     __syncthreads();
-    return (red[0] + red[1]) + (red[2] + red[3]);
+    float t = (red[0] + red[1]) + (red[2] + red[3]);
+#pragma unroll
+    for (int w = 4; w < NT / 64; w += 4) t += (red[w] + red[w + 1]) + (red[w + 2] + red[w + 3]);
+    return t;
 }
 
-SQ_DEVICE v2u pack8(const int (&q)[8])
+SQ_DEVICE v2u pack8(const uint32_t (&q)[8])  // code_bits words -> 8 bytes
 {
-    v2u out;
-    out[0] = (q[0] & 0xff) | ((q[1] & 0xff) << 8) | ((q[2] & 0xff) << 16) | ((uint32_t)(q[3] & 0xff) << 24);
-    out[1] = (q[4] & 0xff) | ((q[5] & 0xff) << 8) | ((q[6] & 0xff) << 16) | ((uint32_t)(q[7] & 0xff) << 24);
-    return out;
+    return v2u{pack4_low_bytes(q[0], q[1], q[2], q[3]), pack4_low_bytes(q[4], q[5], q[6], q[7])};
 }
 
 template <bool BF16, int NV>
@@ -85,12 +89,12 @@ __global__ __launch_bounds__(256) void softmax_quant_kernel(const uint16_t* __re
     for (int i = 0; i < NV; ++i) {
         const int idx = threadIdx.x + i * 256;
         if (idx < nvec) {
-            int q[8];
+            uint32_t q[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 // probability rounded to the 16-bit type first (the softmax output is a 16-bit tensor)
                 const float p16 = load16_bits<BF16>(store16_bits<BF16>(z[i][e] * inv));
-                q[e] = round_code(p16 * 127.0f);
+                q[e] = code_bits(p16 * 127.0f);
             }
             __builtin_nontemporal_store(pack8(q), out + idx);
         }
@@ -140,23 +144,23 @@ __global__ __launch_bounds__(256) void softmax_quant_wave_kernel(const uint16_t*
     for (int i = 0; i < NV; ++i) {
         const int idx = lane + i * 64;
         if (idx < nvec) {
-            int q[8];
+            uint32_t q[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float p16 = load16_bits<BF16>(store16_bits<BF16>(z[i][e] * inv));
-                q[e] = round_code(p16 * 127.0f);
+                q[e] = code_bits(p16 * 127.0f);
             }
             __builtin_nontemporal_store(pack8(q), out + idx);
         }
     }
 }
 
-template <bool BF16, int NV>
-__global__ __launch_bounds__(256) void ln_quant_kernel(const uint16_t* __restrict__ x, int c_i, const float* __restrict__ gamma_f,
+template <bool BF16, int NV, int NT>
+__global__ __launch_bounds__(NT) void ln_quant_kernel(const uint16_t* __restrict__ x, int c_i, const float* __restrict__ gamma_f,
                                                       const float* __restrict__ beta_f, float eps, float* __restrict__ scale,
                                                       int8_t* __restrict__ xq, bool tiled)
 {
-    __shared__ float red[4];
+    __shared__ float red[NT / 64];
     const int64_t row = blockIdx.x;
     const v4u* xr = (const v4u*)(x + row * (int64_t)c_i);
     const int nvec = c_i >> 3;
@@ -164,18 +168,18 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(const uint16_t* __restric
     float sum = 0.0f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-        const int idx = threadIdx.x + i * 256;
+        const int idx = threadIdx.x + i * NT;
         if (idx < nvec) {
             unpack8r<BF16>(__builtin_nontemporal_load(xr + idx), f[i]);
 #pragma unroll
             for (int e = 0; e < 8; ++e) sum += f[i][e];
         }
     }
-    const float mean = block_sum_r(sum, red) / (float)c_i;
+    const float mean = block_sum_r<NT>(sum, red) / (float)c_i;
     float sq = 0.0f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-        const int idx = threadIdx.x + i * 256;
+        const int idx = threadIdx.x + i * NT;
         if (idx < nvec) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -184,12 +188,12 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(const uint16_t* __restric
             }
         }
     }
-    const float var = block_sum_r(sq, red) / (float)c_i;
+    const float var = block_sum_r<NT>(sq, red) / (float)c_i;
     const float rstd = 1.0f / sqrtf(var + eps);
     float m = 0.0f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-        const int idx = threadIdx.x + i * 256;
+        const int idx = threadIdx.x + i * NT;
         if (idx < nvec) {
             const float4 g0 = *(const float4*)(gamma_f + idx * 8), g1 = *(const float4*)(gamma_f + idx * 8 + 4);
             const float4 b0 = *(const float4*)(beta_f + idx * 8), b1 = *(const float4*)(beta_f + idx * 8 + 4);
@@ -202,16 +206,85 @@ __global__ __launch_bounds__(256) void ln_quant_kernel(const uint16_t* __restric
             }
         }
     }
-    const float a = block_max_r(m, red);
+    const float a = block_max_r<NT>(m, red);
     const float r = a > 0.0f ? 127.0f / a : 0.0f;
     if (threadIdx.x == 0) scale[row] = a / 127.0f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-        const int idx = threadIdx.x + i * 256;
+        const int idx = threadIdx.x + i * NT;
         if (idx < nvec) {
-            int q[8];
+            uint32_t q[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) q[e] = round_code(f[i][e] * r);
+            for (int e = 0; e < 8; ++e) q[e] = code_bits(f[i][e] * r);
+            __builtin_nontemporal_store(pack8(q), (v2u*)code_dst(xq, row, idx * 8, c_i, tiled));
+        }
+    }
+}
+
+// One row per wave (hidden sizes up to 2048, where it measures faster than a workgroup per row): the three
+// reductions are cross-lane shuffles, no barriers, and a lane keeps NV 16-byte loads in flight.
+template <bool BF16, int NV>
+__global__ __launch_bounds__(256) void ln_quant_wave_kernel(const uint16_t* __restrict__ x, int64_t t, int c_i,
+                                                           const float* __restrict__ gamma_f, const float* __restrict__ beta_f,
+                                                           float eps, float* __restrict__ scale, int8_t* __restrict__ xq, bool tiled)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= t) return;
+    const v4u* xr = (const v4u*)(x + row * (int64_t)c_i);
+    const int nvec = c_i >> 3;
+    float f[NV][8];
+    float sum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = lane + i * 64;
+        if (idx < nvec) {
+            unpack8r<BF16>(__builtin_nontemporal_load(xr + idx), f[i]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sum += f[i][e];
+        }
+    }
+    const float mean = wave_sum(sum) / (float)c_i;
+    float sq = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = lane + i * 64;
+        if (idx < nvec) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float d = f[i][e] - mean;
+                sq += d * d;
+            }
+        }
+    }
+    const float var = wave_sum(sq) / (float)c_i;
+    const float rstd = 1.0f / sqrtf(var + eps);
+    float m = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = lane + i * 64;
+        if (idx < nvec) {
+            const float4 g0 = *(const float4*)(gamma_f + idx * 8), g1 = *(const float4*)(gamma_f + idx * 8 + 4);
+            const float4 b0 = *(const float4*)(beta_f + idx * 8), b1 = *(const float4*)(beta_f + idx * 8 + 4);
+            const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+            const float b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                f[i][e] = (f[i][e] - mean) * rstd * g[e] + b[e];
+                m = __builtin_fmaxf(m, __builtin_fabsf(f[i][e]));
+            }
+        }
+    }
+    const float a = wave_max(m);
+    const float r = a > 0.0f ? 127.0f / a : 0.0f;
+    if (lane == 0) scale[row] = a / 127.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int idx = lane + i * 64;
+        if (idx < nvec) {
+            uint32_t q[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) q[e] = code_bits(f[i][e] * r);
             __builtin_nontemporal_store(pack8(q), (v2u*)code_dst(xq, row, idx * 8, c_i, tiled));
         }
     }
@@ -260,13 +333,19 @@ sq_status sq_ln_quantize(const void* x, sq_dtype dtype, int64_t t, int64_t c_i, 
     hipStream_t st = (hipStream_t)stream;
     const int nvec = (int)(c_i >> 3);
     const uint16_t* xp = (const uint16_t*)x;
-#define SQ_LN(BF, NV) hipLaunchKernelGGL((ln_quant_kernel<BF, NV>), dim3((unsigned)t), dim3(256), 0, st, xp, (int)c_i, gamma_f, beta_f, eps, scale, xq, tiled)
+    // Measured choice: up to 2048 channels one row per wave; up to 8192 one row per 256-thread workgroup; wider rows
+    // one row per 512-thread workgroup (more loads in flight per row, fewer registers per thread).
+#define SQ_LN(BF, NV, NT) hipLaunchKernelGGL((ln_quant_kernel<BF, NV, NT>), dim3((unsigned)t), dim3(NT), 0, st, xp, (int)c_i, gamma_f, beta_f, eps, scale, xq, tiled)
+#define SQ_LNW(BF, NV) hipLaunchKernelGGL((ln_quant_wave_kernel<BF, NV>), dim3((unsigned)((t + 3) / 4)), dim3(256), 0, st, xp, t, (int)c_i, gamma_f, beta_f, eps, scale, xq, tiled)
     if (dtype == SQ_BF16) {
-        if (nvec <= 256) SQ_LN(true, 1); else if (nvec <= 512) SQ_LN(true, 2); else if (nvec <= 1024) SQ_LN(true, 4); else SQ_LN(true, 8);
+        if (nvec <= 128) SQ_LNW(true, 2); else if (nvec <= 256) SQ_LNW(true, 4); else if (nvec <= 512) SQ_LN(true, 2, 256);
+        else if (nvec <= 1024) SQ_LN(true, 4, 256); else if (nvec <= 1536) SQ_LN(true, 3, 512); else SQ_LN(true, 4, 512);
     } else {
-        if (nvec <= 256) SQ_LN(false, 1); else if (nvec <= 512) SQ_LN(false, 2); else if (nvec <= 1024) SQ_LN(false, 4); else SQ_LN(false, 8);
+        if (nvec <= 128) SQ_LNW(false, 2); else if (nvec <= 256) SQ_LNW(false, 4); else if (nvec <= 512) SQ_LN(false, 2, 256);
+        else if (nvec <= 1024) SQ_LN(false, 4, 256); else if (nvec <= 1536) SQ_LN(false, 3, 512); else SQ_LN(false, 4, 512);
     }
 #undef SQ_LN
+#undef SQ_LNW
     return sq_launch_status();
 }
 
