@@ -586,12 +586,22 @@ Plan make_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split,
     int splits = 1;
     if (allow_split && batch == 1) {
         const int64_t tiles = (int64_t)pl.tiles_m * pl.tiles_n;
-        // Weight-streaming shapes: a few workgroups per CU keep every HBM channel busy.
-        // Compute-bound shapes: split only to fill the last partial round of tiles.
-        const int64_t want = pl.bm == 256 ? kNumCU : 2 * kNumCU;
-        if (tiles < want) {
-            splits = (int)((want + tiles - 1) / tiles);
-            const int max_splits = nk / 8 > 0 ? nk / 8 : 1;  // at least 8 K steps per split
+        const int max_splits = nk / 8 > 0 ? nk / 8 : 1;  // at least 8 K steps per split
+        if (pl.bm == 256) {
+            // Compute-bound tiles: a K split pays (int32 partials through HBM, a second kernel), so it is chosen
+            // by a small time model in microseconds: rounds x (K steps x 0.7 + 12 for fill and epilogue), plus,
+            // when split, 5 for the reduction launch and the partials written and read back at about 4 TB/s
+            // (the write overlaps the GEMM half way).
+            double best = 1e30;
+            for (int sp = 1; sp <= 8 && sp <= max_splits; ++sp) {
+                const int64_t rounds = (tiles * sp + kNumCU - 1) / kNumCU;
+                double t_us = (double)rounds * (((nk + sp - 1) / sp) * 0.7 * pl.bn / 256.0 + 12.0);
+                if (sp > 1) t_us += 5.0 + 1.5 * sp * (double)M * (double)N * 4.0 / 4e6;
+                if (t_us < best * 0.97) { best = t_us; splits = sp; }
+            }
+        } else if (tiles < 2 * kNumCU) {
+            // Weight-streaming shapes: a few workgroups per CU keep every HBM channel busy.
+            splits = (int)((2 * kNumCU + tiles - 1) / tiles);
             if (splits > max_splits) splits = max_splits;
             if (splits > 32) splits = 32;
         }
