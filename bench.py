@@ -174,7 +174,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one MI355X per box); --gpus must be 1. "
-              "Sharding over more GPUs is described in DESIGN.md, not built.", file=sys.stderr)
+              "Sharding over more GPUs is not built.", file=sys.stderr)
         sys.exit(2)
 
     import torch
