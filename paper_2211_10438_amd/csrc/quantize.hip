@@ -275,8 +275,7 @@ void launch_per_token(const uint16_t* x, int64_t ldx, int c_i, int64_t t, const 
     else if (nvec <= 256) SQ_BLOCK(1, 256);
     else if (nvec <= 512) SQ_BLOCK(2, 256);
     else if (nvec <= 1024) SQ_BLOCK(4, 256);
-    else if (nvec <= 1536) SQ_BLOCK(6, 256);
-    else if (nvec <= 2048) SQ_BLOCK(8, 256);
+    else if (nvec <= 2048) SQ_BLOCK(2, 1024);  // measured: from 8192 channels on, 1024 threads per row beat 256
     else if (nvec <= 4096) SQ_BLOCK(4, 1024);
     else if (nvec <= 6144) SQ_BLOCK(6, 1024);
     else if (nvec <= 8192) SQ_BLOCK(8, 1024);
