@@ -25,8 +25,8 @@
 namespace {
 
 constexpr int kDepth = 4;            // pipeline stages
-constexpr int kMaxStageBlocks = 24;  // 1 KB blocks per stage
-constexpr int kSmemBytes = kDepth * kMaxStageBlocks * 1024;
+// 1 KB blocks per stage: 24 for the 4-wave shapes (up to 32 tokens), 32 for the 8-wave shapes
+constexpr int max_stage_blocks(int waves) { return waves == 4 ? 24 : 32; }
 
 struct StreamArgs {
     int gn;          // slabs (workgroups along C_o)
@@ -50,10 +50,12 @@ SQ_DEVICE void wait_stage_landed(int loads)
         case 3: wait_vmcnt_imm<(kDepth - 2) * 3>(); break;
         case 4: wait_vmcnt_imm<(kDepth - 2) * 4>(); break;
         case 5: wait_vmcnt_imm<(kDepth - 2) * 5>(); break;
-        default: wait_vmcnt_imm<(kDepth - 2) * 6>(); break;
+        case 6: wait_vmcnt_imm<(kDepth - 2) * 6>(); break;
+        case 7: wait_vmcnt_imm<(kDepth - 2) * 7>(); break;
+        default: wait_vmcnt_imm<(kDepth - 2) * 8>(); break;
     }
 }
-static_assert(kDepth >= 3 && (kDepth - 2) * (kMaxStageBlocks / 4) <= 63, "depth and vmcnt limits");
+static_assert(kDepth >= 3 && (kDepth - 2) * (max_stage_blocks(4) / 4) <= 63, "depth and vmcnt limits");
 
 // MB: 16-row blocks of A per wave; WM: waves along the token axis (the other NWAVE/WM waves deal the
 // slab's units among themselves); NUW: most units one wave accumulates.  The 8-wave shapes put two
@@ -62,8 +64,8 @@ template <int MB, int WM, int NUW, int NWAVE, bool NT>
 __global__ __launch_bounds__(NWAVE * 64, 1) void gemm_i8_stream_kernel(const GemmArgs p, const StreamArgs q)
 {
     constexpr int WN = NWAVE / WM;
-    constexpr int kLoads = kMaxStageBlocks / NWAVE;
-    __shared__ __attribute__((aligned(1024))) char smem[kSmemBytes];
+    constexpr int kLoads = max_stage_blocks(NWAVE) / NWAVE;
+    __shared__ __attribute__((aligned(1024))) char smem[kDepth * max_stage_blocks(NWAVE) * 1024];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -171,7 +173,7 @@ __global__ __launch_bounds__(NWAVE * 64, 1) void gemm_i8_stream_kernel(const Gem
     switch (cnt) {
         SQ_CASE(0) SQ_CASE(1) SQ_CASE(2) SQ_CASE(3) SQ_CASE(4) SQ_CASE(5) SQ_CASE(6) SQ_CASE(7) SQ_CASE(8)
         SQ_CASE(9) SQ_CASE(10) SQ_CASE(11) SQ_CASE(12) SQ_CASE(13) SQ_CASE(14) SQ_CASE(15) SQ_CASE(16)
-        default: break;
+        default: break;  // NUW <= 16 in every instantiation
     }
 #undef SQ_CASE
     wait_vmcnt_imm<0>();  // the refills issued past the end of the K range have landed
@@ -238,7 +240,7 @@ int num_cus()
 
 // Slab width and K split by a small cost model (seconds):
 //   CU side:  every workgroup moves (A blocks + slab units) KB per K step through its CU's vector cache,
-//             at about 32 GB/s while most loads miss to HBM; workgroups beyond one per CU run in rounds;
+//             at about 26 GB/s while most loads miss to HBM; workgroups beyond one per CU run in rounds;
 //   HBM side: W once plus the int32 partials when K is split, at about 5.5 TB/s;
 //   a K split adds the reduction kernel (launch + reading the partials).
 bool make_stream_plan(int64_t M, int64_t N, int64_t K, int64_t batch, StreamArgs* out)
@@ -249,13 +251,14 @@ bool make_stream_plan(int64_t M, int64_t N, int64_t K, int64_t batch, StreamArgs
     if (units < cus) return false;  // narrow C_o: the tile kernels with split-K cover it
     const int na = M <= 16 ? 1 : M <= 32 ? 2 : M <= 64 ? 4 : 8;
     const int nk = (int)(K >> 6);
-    const double cu_rate = 32e9, hbm_rate = 5.5e12, red_rate = 4e12, red_launch = 5e-6;
+    const double cu_rate = 26e9, hbm_rate = 5.5e12, red_rate = 4e12, red_launch = 5e-6;
+    const int s_max = na == 8 ? 24 : 16;  // widest slab the kernel shapes accumulate
     double best = 1e30, best_cu = 1e30;
     int best_gn = 0, best_gk = 0;
     for (int gk = 1; gk <= 8; ++gk) {
         if (nk % gk) continue;
         if (gk > 1 && (nk / gk < 8 || M <= 32)) continue;
-        for (int s = 1; s <= 16; ++s) {
+        for (int s = 1; s <= s_max; ++s) {
             const int64_t gn = (units + s - 1) / s;
             const int64_t smax = (units + gn - 1) / gn;  // widest slab after dealing the units evenly
             if (s > 1 && (units + s - 2) / (s - 1) == gn) continue;  // same plan as s - 1
@@ -284,7 +287,7 @@ bool make_stream_plan(int64_t M, int64_t N, int64_t K, int64_t batch, StreamArgs
     const int nks = nk / best_gk;
     q.ksub = 1;
     for (int c = 4; c > 1; c >>= 1)
-        if (nblk * c <= kMaxStageBlocks && nks % c == 0) { q.ksub = c; break; }
+        if (nblk * c <= max_stage_blocks(na >= 4 ? 8 : 4) && nks % c == 0) { q.ksub = c; break; }
     q.iters = nks / q.ksub;
     // W is read exactly once: the non-temporal hint keeps it from displacing the activation block in the caches.
     // Measured: +7..12 % at up to 16 tokens; with more tokens it pays only for wide slabs (at least 10 units and
@@ -318,6 +321,6 @@ void sq_stream_gemm_launch(const GemmArgs& a, bool to_i32, bool bf16, bool tiled
         case 5: hipLaunchKernelGGL((gemm_i8_stream_kernel<1, 2, 8, 4, true>), grid, block, 0, st, a, q); break;
         case 8: hipLaunchKernelGGL((gemm_i8_stream_kernel<1, 4, 8, 8, false>), grid, block8, 0, st, a, q); break;
         case 9: hipLaunchKernelGGL((gemm_i8_stream_kernel<1, 4, 8, 8, true>), grid, block8, 0, st, a, q); break;
-        default: hipLaunchKernelGGL((gemm_i8_stream_kernel<2, 4, 8, 8, false>), grid, block8, 0, st, a, q); break;
+        default: hipLaunchKernelGGL((gemm_i8_stream_kernel<2, 4, 12, 8, false>), grid, block8, 0, st, a, q); break;
     }
 }
