@@ -169,8 +169,8 @@ def main():
     ap.add_argument("--tokens", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--probe", action="store_true",
-                    help="counter probe for rocprofv3 --pmc: a 512 MiB device copy (known size) and two steps of the "
-                         "workload, nothing timed, no JSON")
+                    help="counter probe for rocprofv3 --pmc: a 512 MiB device copy (known size), two steps of the "
+                         "workload and two decode steps at 1 / 16 / 128 tokens, nothing timed, no JSON")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one MI355X per box); --gpus must be 1. "
@@ -196,14 +196,34 @@ def main():
         for L in layers:
             run_layer(sq, torch, L)
 
+    def make_decode_step(m):
+        bufs = []
+        for L in layers:
+            xs_in = L["x"][:m].contiguous()
+            nws = sq.workspace_bytes(sq.OP_W8A8_LINEAR, m, L["c_i"], L["c_o"])
+            bufs.append(dict(x=xs_in, xq=sq.empty_codes(m, L["c_i"], sq.TILED),
+                             xs=torch.empty(m, dtype=torch.float32, device="cuda"),
+                             y=torch.empty((m, L["c_o"]), dtype=torch.bfloat16, device="cuda"),
+                             ws=torch.empty(max(nws, 16), dtype=torch.uint8, device="cuda")))
+
+        def dstep():
+            for L, b in zip(layers, bufs):
+                sq.quantize_act(b["x"], sq.PER_TOKEN_DYNAMIC, inv_s=L["inv_s"], out=(b["xq"], b["xs"]), layout=sq.TILED)
+                sq.w8a8_linear(b["xq"], b["xs"], L["wq"], L["w_scale"], torch.bfloat16, out=b["y"], workspace=b["ws"],
+                               layout=sq.TILED)
+        return dstep
+
     if args.probe:
         src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda").random_()
         dst = torch.empty_like(src)
+        dsteps = [make_decode_step(m) for m in (1, 16, 128)]
         for _ in range(2):
             dst.copy_(src)
             step()
+            for ds in dsteps:
+                ds()
         torch.cuda.synchronize()
-        print("probe done: copy of %d bytes + 2 steps" % src.numel())
+        print("probe done: copy of %d bytes + 2 prefill steps + 2 decode steps at 1 / 16 / 128 tokens" % src.numel())
         return
 
     for _ in range(args.warmup):
@@ -244,20 +264,7 @@ def main():
     # all 1.8 GB of int8 weights, far more than any cache holds, so each layer's W comes from HBM every time.
     decode = {}
     for m in (1, 16, 128):
-        bufs = []
-        for L in layers:
-            xs_in = L["x"][:m].contiguous()
-            nws = sq.workspace_bytes(sq.OP_W8A8_LINEAR, m, L["c_i"], L["c_o"])
-            bufs.append(dict(x=xs_in, xq=sq.empty_codes(m, L["c_i"], sq.TILED),
-                             xs=torch.empty(m, dtype=torch.float32, device="cuda"),
-                             y=torch.empty((m, L["c_o"]), dtype=torch.bfloat16, device="cuda"),
-                             ws=torch.empty(max(nws, 16), dtype=torch.uint8, device="cuda")))
-
-        def dstep():
-            for L, b in zip(layers, bufs):
-                sq.quantize_act(b["x"], sq.PER_TOKEN_DYNAMIC, inv_s=L["inv_s"], out=(b["xq"], b["xs"]), layout=sq.TILED)
-                sq.w8a8_linear(b["xq"], b["xs"], L["wq"], L["w_scale"], torch.bfloat16, out=b["y"], workspace=b["ws"],
-                               layout=sq.TILED)
+        dstep = make_decode_step(m)
         for _ in range(args.warmup):
             dstep()
         d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
