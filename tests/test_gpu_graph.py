@@ -1,0 +1,50 @@
+"""The entry points only enqueue kernels on the caller's stream (no allocation, no memset, no synchronisation), so a
+decode step can be captured into a HIP graph and replayed.  Every replay is checked against the eager result, with
+eager work and synchronisations between the replays."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2211_10438_amd import binding as sq
+from paper_2211_10438_amd import synth
+from tests._util import F16, dev, to_dev_16
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("t,c_i,c_o,mode", [(16, 1024, 4096, sq.PER_TOKEN_DYNAMIC),    # weight streaming
+                                            (16, 4096, 1024, sq.PER_TOKEN_DYNAMIC),    # split-K tiles + reduction
+                                            (128, 4096, 4096, sq.PER_TENSOR_DYNAMIC),  # streaming with a K split, O2 quantizer
+                                            (300, 512, 768, sq.PER_TOKEN_DYNAMIC)])    # prefill tiles
+def test_graph_replay_matches_eager(t, c_i, c_o, mode):
+    print(f"[case] graph replay t={t} c_i={c_i} c_o={c_o} mode={mode}", flush=True)
+    w = synth.weights(c_i, c_o, 4242)
+    wq, ws = sq.prepare_weight(to_dev_16(w, F16), None, layout=sq.TILED)
+    xs_host = [synth.normal_fp16((t, c_i), 5000 + i) for i in range(3)]
+    x = to_dev_16(xs_host[0], F16).clone()
+    xq = sq.empty_codes(t, c_i, sq.TILED)
+    scale = torch.empty(t if mode == sq.PER_TOKEN_DYNAMIC else 1, dtype=torch.float32, device="cuda")
+    y = torch.empty((t, c_o), dtype=torch.float16, device="cuda")
+    qws = torch.empty(64, dtype=torch.uint8, device="cuda")
+    gws = torch.empty(max(sq.workspace_bytes(sq.OP_W8A8_LINEAR, t, c_i, c_o), 16), dtype=torch.uint8, device="cuda")
+
+    def step():
+        sq.quantize_act(x, mode, out=(xq, scale), workspace=qws, layout=sq.TILED)
+        sq.w8a8_linear(xq, scale, wq, ws, torch.float16, out=y, workspace=gws, layout=sq.TILED)
+
+    step()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for i in range(3):
+        x.copy_(to_dev_16(xs_host[i], F16))
+        y.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        got = y.clone()
+        y.zero_()
+        step()  # eager, same inputs
+        torch.cuda.synchronize()
+        assert torch.equal(got, y), f"replay {i} differs from the eager result"
+        assert bool(torch.isfinite(y.float()).all()) and float(y.float().abs().max()) > 0.0
