@@ -279,6 +279,20 @@ def main():
                            "frac_hbm_peak": round(dbytes / dms / 1e6 / PEAK_HBM_GBS, 4),
                            "tops": round(sum(2.0 * m * L["c_i"] * L["c_o"] for L in layers) / dms / 1e9, 2)}
 
+    # What the INT8 matrix pipes sustain when fed from registers (no memory traffic), on the codes of this workload:
+    # the nominal peak assumes 2.4 GHz, the chip holds about 1.6 GHz under a sustained MFMA load.
+    probe_data = layers[0]["wq"]
+    probe_data = (probe_data._base if probe_data._base is not None else probe_data).reshape(-1)[: 2048 * 49152]
+    probe_iters = 20000
+    sq.probe_mfma_i8(probe_data, 2048, 2000)
+    torch.cuda.synchronize()
+    p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    p0.record()
+    probe_ops = sq.probe_mfma_i8(probe_data, 2048, probe_iters)
+    p1.record()
+    torch.cuda.synchronize()
+    mfma_only_tops = probe_ops / (p0.elapsed_time(p1) * 1e-3) / 1e12
+
     # HBM-side traffic of the GEMM launches: measured separately with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on
     # `bench.py --probe` (counters cannot be read from inside this process); the summary is kept under profiles/.
     traffic = None
@@ -306,9 +320,13 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "gemm_i8_kernel (256x256 / 256x192 tiles, INT8 MFMA GEMM + dequant epilogue)",
                      "achieved": round(gemm_tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s",
                      "frac": round(gemm_tops / PEAK_INT8_TOPS, 4), "traffic": traffic,
+                     "mfma_only_loop_tops": round(mfma_only_tops, 1),
+                     "frac_of_mfma_only_loop": round(gemm_tops / mfma_only_tops, 4),
                      "note": "int8 multiply-accumulate counted as 2 ops; achieved = sum of 2*T*C_i*C_o over the four "
                              "layers / sum of their average GEMM launch durations (HIP events); traffic = HBM-side "
-                             "bytes (FETCH_SIZE + WRITE_SIZE, calibrated on a copy) averaged over the four launches"},
+                             "bytes (FETCH_SIZE + WRITE_SIZE, calibrated on a copy) averaged over the four launches; "
+                             "mfma_only_loop_tops = register-fed MFMA loop on the same weight codes, 2048 workgroups x 8 "
+                             "waves (what the matrix pipes sustain at the clock the chip holds under this load)"},
         "per_layer_us": {L["name"]: {"quantize": round(L["quant_us"], 1), "gemm": round(L["gemm_us"], 1),
                                      "gemm_tops": round(L["ops"] / L["gemm_us"] / 1e6, 1)} for L in layers},
         "quantize_pass": {"bound": "hbm", "achieved_GBs": round(quant_bytes / (quant_ms * 1e-3) / 1e9, 1),

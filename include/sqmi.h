@@ -175,6 +175,13 @@ sq_status sq_ln_quantize(const void* x, sq_dtype dtype, int64_t t, int64_t c_i, 
                          const float* beta_f, float eps, float* scale, int8_t* xq, sq_layout xq_layout,
                          void* stream);
 
+/* Measurement aid, not part of the method: runs `iters` rounds of 8 register-fed INT8 MFMAs (32x32x32) on each of
+ * the 8 waves of `workgroups` workgroups, i.e. workgroups * 8 * iters * 8 * 65536 integer operations, with no
+ * memory traffic inside the loop.  The operand registers are filled once from `data` (device int8, at least
+ * workgroups * 49152 bytes: the bit patterns matter, the sustained clock depends on them); sink: device int32
+ * [workgroups * 512], overwritten.  bench.py times it to report the GEMM against what the matrix pipes sustain. */
+sq_status sq_probe_mfma_i8(const int8_t* data, size_t data_bytes, int workgroups, int iters, int32_t* sink, void* stream);
+
 /* Workspace size in bytes for `op` at the given problem size (0 if none is needed).  For
  * SQ_OP_W8A8_BMM pass (m, k, n) as (t, c_i, c_o). */
 size_t sq_workspace_bytes(sq_op op, int64_t t, int64_t c_i, int64_t c_o);

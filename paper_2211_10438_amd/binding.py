@@ -23,7 +23,7 @@ ROW_MAJOR, TILED = 0, 1
 EXPORTS = (
     "sq_status_string", "sq_smooth_scales", "sq_act_absmax_per_channel", "sq_weight_absmax_per_in_channel",
     "sq_prepare_weight", "sq_quantize_act", "sq_w8a8_linear", "sq_w8a8_linear_q8", "sq_i8_gemm_i32", "sq_w8a8_bmm",
-    "sq_softmax_quant_p", "sq_ln_quantize", "sq_workspace_bytes", "sq_tiled_bytes",
+    "sq_softmax_quant_p", "sq_ln_quantize", "sq_workspace_bytes", "sq_tiled_bytes", "sq_probe_mfma_i8",
 )
 
 
@@ -55,6 +55,7 @@ def lib() -> ctypes.CDLL:
                                         ctypes.c_size_t, vp]
         L.sq_i8_gemm_i32.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, ctypes.c_size_t, vp]
         L.sq_w8a8_bmm.argtypes = [vp, vp, i32, f32, vp, i32, i64, i64, i64, i64, i64, i64, i64, vp]
+        L.sq_probe_mfma_i8.argtypes = [vp, ctypes.c_size_t, i32, i32, vp, vp]
         L.sq_softmax_quant_p.argtypes = [vp, i32, i64, i64, vp, vp]
         L.sq_ln_quantize.argtypes = [vp, i32, i64, i64, vp, vp, f32, vp, vp, i32, vp]
         L.sq_workspace_bytes.restype = ctypes.c_size_t
@@ -272,6 +273,14 @@ def softmax_quant_p(s: torch.Tensor, out=None) -> torch.Tensor:
     _check(lib().sq_softmax_quant_p(_dev(s, None, "s"), _dt(s), rows, cols, _dev(pq, torch.int8, "pq"), _stream()),
            "sq_softmax_quant_p")
     return pq
+
+
+def probe_mfma_i8(data: torch.Tensor, workgroups: int, iters: int) -> float:
+    """Measurement aid: enqueue the MFMA-only loop; returns the number of integer operations it performs."""
+    sink = torch.empty(workgroups * 512, dtype=torch.int32, device=data.device)
+    _check(lib().sq_probe_mfma_i8(_dev(data, torch.int8, "data"), data.numel(), workgroups, iters, sink.data_ptr(), _stream()),
+           "sq_probe_mfma_i8")
+    return float(workgroups) * 8 * iters * 8 * 65536
 
 
 def ln_quantize(x: torch.Tensor, gamma_f: torch.Tensor, beta_f: torch.Tensor, eps: float = 1e-5, out=None,
