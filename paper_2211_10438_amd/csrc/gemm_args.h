@@ -58,3 +58,7 @@ SQ_DEVICE uint32_t dequant_one(int acc, float c, float bias, bool has_bias, bool
 // the caller points at a workspace) and the split-K reduction kernel finishes the job.
 int sq_stream_gemm_splits(int64_t M, int64_t N, int64_t K, int64_t batch);
 void sq_stream_gemm_launch(const GemmArgs& a, bool to_i32, bool bf16, bool tiled, hipStream_t st);
+
+// Strip kernel for attention scores (bmm_strip.hip): B = [N, K] with K <= 128, alpha-only epilogue.
+bool sq_strip_bmm_eligible(int64_t M, int64_t N, int64_t K, int64_t batch);
+void sq_strip_bmm_launch(const GemmArgs& a, int batch, bool bf16, hipStream_t st);

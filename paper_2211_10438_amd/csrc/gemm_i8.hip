@@ -793,6 +793,10 @@ sq_status sq_internal_bmm(const int8_t* a_, const int8_t* b_, int trans_b, float
     a.ldb = trans_b ? k : n;  // trans_b: rows of B are K-contiguous; otherwise B is [k, n]
     a.strideA = stride_a; a.strideB = stride_b; a.strideC = stride_c;
     a.C = c; a.alpha = alpha;
+    if (trans_b && sq_strip_bmm_eligible(m, n, k, batch)) {
+        sq_strip_bmm_launch(a, (int)batch, out == SQ_BF16, (hipStream_t)stream);
+        return sq_launch_status();
+    }
     return run_gemm(a, batch, false, out == SQ_BF16, nullptr, 0, (hipStream_t)stream, !trans_b);
 }
 
