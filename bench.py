@@ -110,9 +110,10 @@ def other_configs(sq, torch):
         sc = torch.empty((bh, s_len, s_len), dtype=torch.float16, device="cuda")
         pq = torch.empty((bh, s_len, s_len), dtype=torch.int8, device="cuda")
         o = torch.empty((bh, s_len, d), dtype=torch.float16, device="cuda")
-        t1 = _time_us(torch, lambda: sq.w8a8_bmm(q, k, True, 2e-5, torch.float16, out=sc), iters=5, warm=1)
-        t2 = _time_us(torch, lambda: sq.softmax_quant_p(sc, out=pq), iters=5, warm=1)
-        t3 = _time_us(torch, lambda: sq.w8a8_bmm(pq, v, False, 1e-4, torch.float16, out=o), iters=5, warm=1)
+        # (the first launches after the multi-GB allocations run slower than the steady state: warm up longer)
+        t1 = _time_us(torch, lambda: sq.w8a8_bmm(q, k, True, 2e-5, torch.float16, out=sc), iters=10, warm=5)
+        t2 = _time_us(torch, lambda: sq.softmax_quant_p(sc, out=pq), iters=8, warm=2)
+        t3 = _time_us(torch, lambda: sq.w8a8_bmm(pq, v, False, 1e-4, torch.float16, out=o), iters=8, warm=2)
         b1 = 2.0 * bh * s_len * d + 2.0 * bh * s_len * s_len
         b2 = 3.0 * bh * s_len * s_len
         b3 = bh * s_len * s_len + 3.0 * bh * s_len * d
@@ -171,6 +172,9 @@ def main():
     ap.add_argument("--probe", action="store_true",
                     help="counter probe for rocprofv3 --pmc: a 512 MiB device copy (known size), two steps of the "
                          "workload and two decode steps at 1 / 16 / 128 tokens, nothing timed, no JSON")
+    ap.add_argument("--probe-attention", action="store_true",
+                    help="counter probe for rocprofv3 --pmc: a 512 MiB device copy, then the INT8 attention chain "
+                         "(scores, softmax + P quantization, P V) at 768 heads x 2048 x 128 twice, nothing timed, no JSON")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one MI355X per box); --gpus must be 1. "
@@ -184,6 +188,24 @@ def main():
     sq.lib()  # fail loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.probe_attention:
+        bh, s_len, d = 768, 2048, 128
+        g = torch.Generator(device="cuda")
+        g.manual_seed(78)
+        q, k, v = (torch.randint(-127, 128, (bh, s_len, d), dtype=torch.int8, device="cuda", generator=g) for _ in range(3))
+        sc = torch.empty((bh, s_len, s_len), dtype=torch.float16, device="cuda")
+        pq = torch.empty((bh, s_len, s_len), dtype=torch.int8, device="cuda")
+        o = torch.empty((bh, s_len, d), dtype=torch.float16, device="cuda")
+        src = torch.empty(512 << 20, dtype=torch.uint8, device="cuda").random_()
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            dst.copy_(src)
+            sq.w8a8_bmm(q, k, True, 2e-5, torch.float16, out=sc)
+            sq.softmax_quant_p(sc, out=pq)
+            sq.w8a8_bmm(pq, v, False, 1e-4, torch.float16, out=o)
+        torch.cuda.synchronize()
+        print("probe done: copy of %d bytes + 2 attention chains at %d heads x %d x %d" % (src.numel(), bh, s_len, d))
+        return
     t = args.tokens
     desc = [(l.name, l.c_i, l.c_o) for l in synth.OPT175B_LINEARS]
     layers = []
