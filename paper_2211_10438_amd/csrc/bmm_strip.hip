@@ -176,8 +176,9 @@ __global__ __launch_bounds__(320, WPE) void bmm_strip_kernel(const GemmArgs p, c
 
 bool sq_strip_bmm_eligible(int64_t M, int64_t N, int64_t K, int64_t batch)
 {
-    // whole 128-column tiles, the contraction in one LDS row, enough rows that Q reuse pays
-    return M > 128 && K <= 128 && (K & 15) == 0 && (N & 127) == 0 && batch >= 1;
+    // whole 128-column tiles, the contraction in one LDS row, enough rows that Q reuse pays; the grid is one-dimensional
+    const int64_t wgs = batch * ((M + SB_BM - 1) / SB_BM) * (N / SB_BN);  // upper bound: every strip split into single tiles
+    return M > 128 && K <= 128 && (K & 15) == 0 && (N & 127) == 0 && batch >= 1 && wgs < ((int64_t)1 << 31);
 }
 
 void sq_strip_bmm_launch(const GemmArgs& a, int batch, bool bf16, hipStream_t st)
