@@ -48,3 +48,37 @@ def test_graph_replay_matches_eager(t, c_i, c_o, mode):
         torch.cuda.synchronize()
         assert torch.equal(got, y), f"replay {i} differs from the eager result"
         assert bool(torch.isfinite(y.float()).all()) and float(y.float().abs().max()) > 0.0
+
+
+def test_graph_replay_attention_chain():
+    """Scores (strip kernel) -> softmax + P quantization -> P V captured as one graph."""
+    b, s, d = 6, 384, 128
+    print(f"[case] graph replay attention b={b} s={s} d={d}", flush=True)
+    hosts = [[synth.int8_codes((b, s, d), 7000 + 10 * i + j) for j in range(3)] for i in range(3)]
+    q, k, v = (dev(hosts[0][j]).clone() for j in range(3))
+    sc = torch.empty((b, s, s), dtype=torch.float16, device="cuda")
+    pq = torch.empty((b, s, s), dtype=torch.int8, device="cuda")
+    o = torch.empty((b, s, d), dtype=torch.float16, device="cuda")
+
+    def step():
+        sq.w8a8_bmm(q, k, True, 3e-4, torch.float16, out=sc)
+        sq.softmax_quant_p(sc, out=pq)
+        sq.w8a8_bmm(pq, v, False, 1e-3, torch.float16, out=o)
+
+    step()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for i in range(3):
+        for t, h in zip((q, k, v), hosts[i]):
+            t.copy_(dev(h))
+        o.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        got, got_p = o.clone(), pq.clone()
+        o.zero_()
+        step()
+        torch.cuda.synchronize()
+        assert torch.equal(got, o) and torch.equal(got_p, pq), f"replay {i} differs from the eager result"
+        assert float(o.float().abs().max()) > 0.0
