@@ -339,7 +339,7 @@ def main():
         "config": {"workload": f"opt175b_linears_hidden12288_M{t}: qkv+out_proj+fc1+fc2, per-token dynamic act, "
                                "per-tensor weight, bf16 out, 0.5% outlier channels x80, alpha 0.5"},
         "pct_int8_mfma_peak": round(100.0 * tops / PEAK_INT8_TOPS, 2),
-        "roofline": {"bound": "mfma", "kernel": "gemm_i8_kernel (256x256 / 256x192 tiles, INT8 MFMA GEMM + dequant epilogue)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_i8_kernel (256x384 / 256x256 tiles, INT8 MFMA GEMM + dequant epilogue)",
                      "achieved": round(gemm_tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s",
                      "frac": round(gemm_tops / PEAK_INT8_TOPS, 4), "traffic": traffic,
                      "mfma_only_loop_tops": round(mfma_only_tops, 1),

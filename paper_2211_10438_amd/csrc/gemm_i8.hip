@@ -7,7 +7,7 @@
 //
 // Design (CDNA4):
 //  * v_mfma_i32_32x32x32_i8, one wave owns a (MI*32) x (NI*32) block of accumulators; the prefill
-//    tiles (256x256, 256x192) run 8 waves = 2 per SIMD, so one wave's barrier / LDS waits are
+//    tiles (256x256, 256x192, 256x384) run 8 waves = 2 per SIMD, so one wave's barrier / LDS waits are
 //    covered by the other wave's MFMAs.
 //  * Operand tiles travel HBM -> LDS with global_load_lds_dwordx4 (no VGPR staging), NSTAGE deep.
 //    LDS holds a tile as 16-row blocks of 1 KB, row-major (64 B per row) with the four 16-byte
@@ -63,7 +63,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
     static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
     static_assert(NSTAGE >= (BT ? 4 : 3) && (NSTAGE - 2) * LPS <= 63, "pipeline depth exceeds the 6-bit vmcnt");
     static_assert(NSTAGE * STAGE <= 160 * 1024, "LDS budget");
-    constexpr int EPI_BYTES = EPI == EPI_DEQUANT ? BM * (BN * 2 + 16) : 0;
+    // The epilogue stages the 16-bit tile in LDS; a tile too large for that goes in EG groups of GR rows.
+    constexpr int EG = BM * (BN * 2 + 16) <= 160 * 1024 ? 1 : 2;
+    constexpr int GR = BM / EG;
+    constexpr int EPI_BYTES = EPI == EPI_DEQUANT ? GR * (BN * 2 + 16) : 0;
     // BT: behind the ring, three buffers hold the B tile in MFMA operand layout (see transpose_stage).
     constexpr int BOP = NSTAGE * STAGE;
     constexpr int RING_BYTES = (ONESHOT ? NSTAGE - 1 : NSTAGE) * STAGE + (BT ? 3 * B_BYTES : 0);
@@ -379,15 +382,25 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
         // apart) on different banks.
         constexpr int PITCH = BN * 2 + 16;
         constexpr int CPR = BN / 8;  // 16-byte chunks per tile row
-        static_assert(BM * PITCH <= SMEM_BYTES, "epilogue staging must fit in the LDS allocation");
+        static_assert(GR * PITCH <= SMEM_BYTES && GR % 32 == 0, "epilogue staging must fit in the LDS allocation");
         uint16_t* C = (uint16_t*)p.C + (int64_t)batch * p.strideC;
         const uint16_t* R = (const uint16_t*)p.residual;
         const bool vec_ok = (p.N & 7) == 0;  // 16-byte chunks never straddle the row end and stay aligned
-        __builtin_amdgcn_s_barrier();        // every wave has finished reading operand tiles from LDS
+        const float ws = (p.x_scale && !p.w_per_channel) ? p.w_scale[0] : 0.0f;
+        const float xs0 = (p.x_scale && !p.per_token) ? p.x_scale[0] : 0.0f;
+        float rq = 0.0f;
+        if (p.q8_step) {
+            const float delta = p.q8_step[0];
+            rq = delta > 0.0f ? 1.0f / delta : 0.0f;
+        }
+#pragma unroll
+        for (int eg = 0; eg < EG; ++eg) {
+        const int g0 = eg * GR;  // first tile row of this group
+        __syncthreads();  // operand reads (first group) or the previous group's stores out of LDS are done
         if (R) {
-            for (int q = threadIdx.x; q < BM * CPR; q += NW * 64) {
+            for (int q = threadIdx.x; q < GR * CPR; q += NW * 64) {
                 const int r = q / CPR, c8 = (q - r * CPR) * 8;
-                const int row = m0 + r, col = n0 + c8;
+                const int row = m0 + g0 + r, col = n0 + c8;
                 v4u val = {0, 0, 0, 0};
                 if (row < p.M && col < p.N) {
                     const uint16_t* src = R + (int64_t)row * p.N + col;
@@ -404,16 +417,15 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
             }
             __syncthreads();
         }
-        const float ws = (p.x_scale && !p.w_per_channel) ? p.w_scale[0] : 0.0f;
-        const float xs0 = (p.x_scale && !p.per_token) ? p.x_scale[0] : 0.0f;
         // The optional terms are compile-time flags inside the loop (one uniform switch outside) so the
         // common cases cost convert + multiply + round per element and one 8-byte LDS write per four.
         auto phase1 = [&](auto HB, auto RL, auto HR) {
             constexpr bool has_bias = decltype(HB)::value, relu = decltype(RL)::value, has_res = decltype(HR)::value;
 #pragma unroll
             for (int i = 0; i < MI; ++i) {
-                const int lrow = wm * WM + i * 32 + row_l;
-                const int row = m0 + lrow;
+                if (EG > 1 && (wm * WM + i * 32) / GR != eg) continue;  // rows of another group
+                const int lrow = wm * WM + i * 32 + row_l - g0;
+                const int row = m0 + g0 + lrow;
                 const float xrow = p.x_scale ? (p.per_token ? p.x_scale[row < p.M ? row : p.M - 1] : xs0) : 0.0f;
                 float c;
                 if (p.x_scale) c = xrow * ws;
@@ -458,14 +470,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
             default: phase1(T_{}, T_{}, T_{}); break;
         }
         __syncthreads();
-        float rq = 0.0f;
-        if (p.q8_step) {
-            const float delta = p.q8_step[0];
-            rq = delta > 0.0f ? 1.0f / delta : 0.0f;
-        }
-        for (int q = threadIdx.x; q < BM * CPR; q += NW * 64) {
+        for (int q = threadIdx.x; q < GR * CPR; q += NW * 64) {
             const int r = q / CPR, c8 = (q - r * CPR) * 8;
-            const int row = m0 + r, col = n0 + c8;
+            const int row = m0 + g0 + r, col = n0 + c8;
             if (row < p.M && col < p.N) {
                 const v4u val = *(const v4u*)(smem + r * PITCH + c8 * 2);
                 if (p.q8_step) {
@@ -495,6 +502,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
                 }
             }
         }
+        }  // row groups
     }
 }
 
@@ -535,6 +543,7 @@ struct Plan {
     int cfg;     // 0: 256x256 (prefill)  1: 128x256  2: 64x256  3: 32x256  5: 256x128 B^T  6: 256x192
                  // 7: 128x128, three workgroups per CU (short K: the output stream dominates)
                  // 8: 128x128, K <= 128 fetched in one go, four workgroups per CU
+                 // 9: 256x384 (a round of tiles saved on wide outputs)
     int bm, bn;
     int splits, iters_per_split;
     int tiles_m, tiles_n;
@@ -573,9 +582,20 @@ Plan make_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split,
         pl.cfg = 0;
         pl.bm = 256;
         const int64_t tm = (M + 255) / 256;
-        const int64_t r256 = (tm * ((N + 255) / 256) * batch + kNumCU - 1) / kNumCU * 256;
-        const int64_t r192 = (tm * ((N + 191) / 192) * batch + kNumCU - 1) / kNumCU * 224;
-        if (r192 < r256) { pl.cfg = 6; pl.bn = 192; }
+        const int64_t rounds256 = (tm * ((N + 255) / 256) * batch + kNumCU - 1) / kNumCU;
+        const int64_t rounds192 = (tm * ((N + 191) / 192) * batch + kNumCU - 1) / kNumCU;
+        const bool use192 = rounds192 * 224 < rounds256 * 256;
+        if (use192) { pl.cfg = 6; pl.bn = 192; }
+        // 256x384 tiles (192 accumulator registers per lane, the whole 160 KB of LDS, epilogue in two halves):
+        // 4 % fewer cycles per multiply-accumulate in the K loop but a longer fill and epilogue.  Measured per tile,
+        // in microseconds: K steps x 0.59 + 6 (192 wide), x 0.70 + 18 (256), x 1.005 + 31 (384).  Taken where
+        // that model promises at least 4 % (it pays when the wider tile saves a round of tiles: 2048 tokens into
+        // 36864 or 12288 channels, not into 49152).
+        const int64_t rounds384 = (tm * ((N + 383) / 384) * batch + kNumCU - 1) / kNumCU;
+        const double nks = (double)((K + 63) / 64);
+        const double t_now = use192 ? rounds192 * (nks * 0.588 + 6.0) : rounds256 * (nks * 0.70 + 18.0);
+        const double t384 = rounds384 * (nks * 1.005 + 31.0);
+        if (t384 < 0.96 * t_now) { pl.cfg = 9; pl.bn = 384; }
     }
     else if (M > 64) { pl.cfg = 1; pl.bm = 128; }
     else if (M > 32) { pl.cfg = 2; pl.bm = 64; }
@@ -628,6 +648,7 @@ void launch_cfg(const Plan& pl, const GemmArgs& a, int batch, hipStream_t st, bo
         case 2: SQ_LAUNCH(64, 256, 1, 4, 7); break;
         case 3: SQ_LAUNCH(32, 256, 1, 4, 8); break;
         case 6: SQ_LAUNCH(256, 192, 4, 2, 4); break;
+        case 9: SQ_LAUNCH(256, 384, 2, 4, 4); break;
         case 8:
             if (tiled) hipLaunchKernelGGL((gemm_i8_kernel<128, 128, 2, 2, 3, EPI, BF16, LAY_TILED, 4, true>), grid, dim3(256), 0, st, a);
             else hipLaunchKernelGGL((gemm_i8_kernel<128, 128, 2, 2, 3, EPI, BF16, LAY_ROWS, 4, true>), grid, dim3(256), 0, st, a);
