@@ -20,7 +20,14 @@ template <bool BF16> SQ_DEVICE void unpack8r(const v4u raw, float (&f)[8])
 // matters (x > -6), far below the half-ulp of the 16-bit rounding that follows; results below 2^-126 come
 // out as 0, which is what their codes are anyway.  The library routine costs ~20 instructions per call and
 // made this pass ALU-bound.
-SQ_DEVICE float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896340736f); }
+// e^(z - m) with the subtraction folded into one fused multiply-add: 2^(z * log2(e) + nm), nm = -m * log2(e)
+// rounded once per row.  Against (z - m) * log2(e) the argument differs by at most ~2 of its ulps (|argument| < 64),
+// i.e. a relative 1e-5 in the result, far below the half-ulp of the 16-bit rounding that follows.
+SQ_DEVICE float fast_exp_shifted(float z, float nm) { return __builtin_amdgcn_exp2f(__builtin_fmaf(z, 1.44269504088896340736f, nm)); }
+// Code of a probability p16 in [0, 1] (already rounded to the 16-bit type): round(p16 * 127) needs no clamp, and
+// p16 * 127 is exact in fp32 (11 x 7 significant bits), so the fused multiply-add with 1.5 * 2^23 rounds exactly
+// once, to nearest-even, like the separate multiply and add of code_bits.
+SQ_DEVICE uint32_t prob_code_bits(float p16) { return __builtin_bit_cast(uint32_t, __builtin_fmaf(p16, 127.0f, 12582912.0f)); }
 
 template <int NT = 256> SQ_DEVICE float block_max_r(float v, float* red)
 {
@@ -70,6 +77,7 @@ __global__ __launch_bounds__(256) void softmax_quant_kernel(const uint16_t* __re
         }
     }
     mx = block_max_r(mx, red);
+    const float nmx = -mx * 1.44269504088896340736f;
     float sum = 0.0f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
@@ -77,7 +85,7 @@ __global__ __launch_bounds__(256) void softmax_quant_kernel(const uint16_t* __re
         if (idx < nvec) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                z[i][e] = fast_exp(z[i][e] - mx);
+                z[i][e] = fast_exp_shifted(z[i][e], nmx);
                 sum += z[i][e];
             }
         }
@@ -94,7 +102,7 @@ __global__ __launch_bounds__(256) void softmax_quant_kernel(const uint16_t* __re
             for (int e = 0; e < 8; ++e) {
                 // probability rounded to the 16-bit type first (the softmax output is a 16-bit tensor)
                 const float p16 = load16_bits<BF16>(store16_bits<BF16>(z[i][e] * inv));
-                q[e] = code_bits(p16 * 127.0f);
+                q[e] = prob_code_bits(p16);
             }
             __builtin_nontemporal_store(pack8(q), out + idx);
         }
@@ -125,6 +133,7 @@ __global__ __launch_bounds__(256) void softmax_quant_wave_kernel(const uint16_t*
         }
     }
     mx = wave_max(mx);
+    const float nmx = -mx * 1.44269504088896340736f;
     float sum = 0.0f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
@@ -132,7 +141,7 @@ __global__ __launch_bounds__(256) void softmax_quant_wave_kernel(const uint16_t*
         if (idx < nvec) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                z[i][e] = fast_exp(z[i][e] - mx);
+                z[i][e] = fast_exp_shifted(z[i][e], nmx);
                 sum += z[i][e];
             }
         }
@@ -148,7 +157,7 @@ __global__ __launch_bounds__(256) void softmax_quant_wave_kernel(const uint16_t*
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float p16 = load16_bits<BF16>(store16_bits<BF16>(z[i][e] * inv));
-                q[e] = code_bits(p16 * 127.0f);
+                q[e] = prob_code_bits(p16);
             }
             __builtin_nontemporal_store(pack8(q), out + idx);
         }
