@@ -15,7 +15,8 @@ pytestmark = pytest.mark.gpu
 @pytest.mark.parametrize("t,c_i,c_o,mode", [(16, 1024, 4096, sq.PER_TOKEN_DYNAMIC),    # weight streaming
                                             (16, 4096, 1024, sq.PER_TOKEN_DYNAMIC),    # split-K tiles + reduction
                                             (128, 4096, 4096, sq.PER_TENSOR_DYNAMIC),  # streaming with a K split, O2 quantizer
-                                            (300, 512, 768, sq.PER_TOKEN_DYNAMIC)])    # prefill tiles
+                                            (300, 512, 768, sq.PER_TOKEN_DYNAMIC),     # prefill tiles
+                                            (2048, 12288, 12288, sq.PER_TOKEN_DYNAMIC)])  # the 256x384 tile (uses scratch memory)
 def test_graph_replay_matches_eager(t, c_i, c_o, mode):
     print(f"[case] graph replay t={t} c_i={c_i} c_o={c_o} mode={mode}", flush=True)
     w = synth.weights(c_i, c_o, 4242)
