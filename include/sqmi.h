@@ -16,6 +16,7 @@
  *    stream) and never synchronize; buffers must stay alive until the stream has run the work.
  *  - Errors are returned as sq_status; argument errors are detected on the host before any launch.
  *  - Device tensors must be 16-byte aligned; C_i (the contraction length) must be a multiple of 16.
+ *    Further limits are stated with the entry point they belong to; all of them are checked on the host.
  *  - Fixed arithmetic (so that int8 codes are reproducible bit for bit): round-half-to-even;
  *    X / Delta is evaluated as X * r with r = fl32(127 / absmax) (r = fl32(1 / Delta) in static
  *    mode); codes lie in [-127, 127] (static mode saturates); absmax = 0 gives Delta = 0 and codes
@@ -36,7 +37,8 @@ typedef enum {
     SQ_OK = 0,
     SQ_ERR_NULL = 1,        /* a required pointer is NULL */
     SQ_ERR_SHAPE = 2,       /* non-positive / overflowing / inconsistent dimension */
-    SQ_ERR_ALIGN = 3,       /* pointer not 16-byte aligned or C_i / stride not a multiple of 16 */
+    SQ_ERR_ALIGN = 3,       /* pointer not 16-byte aligned, or a dimension / stride not a multiple of what the entry
+                               point asks for (C_i % 16 everywhere; see each declaration) */
     SQ_ERR_UNSUPPORTED = 4, /* enum value or parameter outside the supported set */
     SQ_ERR_WORKSPACE = 5,   /* workspace missing or smaller than sq_workspace_bytes() */
     SQ_ERR_HIP = 6          /* the HIP runtime reported an error at launch */
@@ -88,7 +90,8 @@ sq_status sq_act_absmax_per_channel(const void* x, sq_dtype dtype, int64_t t, in
                                     float* out, void* stream);
 
 /* Weight statistic of Eq. 4: out_j = max_n |W_jn| (row j of W = input channel j).  w: device
- * [c_i, c_o] row-major 16-bit (the paper's W orientation); out: device fp32 [c_i]. */
+ * [c_i, c_o] row-major 16-bit (the paper's W orientation); out: device fp32 [c_i].
+ * Limits: c_o % 8 == 0 (SQ_ERR_ALIGN). */
 sq_status sq_weight_absmax_per_in_channel(const void* w, sq_dtype dtype, int64_t c_i, int64_t c_o,
                                           float* out, void* stream);
 
@@ -99,7 +102,9 @@ sq_status sq_weight_absmax_per_in_channel(const void* w, sq_dtype dtype, int64_t
  * w: device [c_i, c_o] row-major 16-bit; s: device fp32 [c_i] or NULL (s = 1);
  * wq: device int8 [c_o, c_i] (transposed: contraction index contiguous) in layout `wq_layout`;
  * w_scale: device fp32 [1], or [c_o] with w_scale_per_channel.
- * workspace: device, >= sq_workspace_bytes(SQ_OP_PREPARE_WEIGHT, 0, c_i, c_o) bytes. */
+ * workspace: device, >= sq_workspace_bytes(SQ_OP_PREPARE_WEIGHT, 0, c_i, c_o) bytes.
+ * Limits: c_i % 16 == 0 and c_o % 8 == 0 (SQ_ERR_ALIGN); c_i <= 64 * 65535 (SQ_ERR_SHAPE); SQ_TILED needs
+ * c_i % 64 == 0. */
 sq_status sq_prepare_weight(const void* w, sq_dtype dtype, const float* s, int64_t c_i, int64_t c_o,
                             int8_t* wq, sq_layout wq_layout, float* w_scale, int w_scale_per_channel,
                             void* workspace, size_t ws_bytes, void* stream);
@@ -154,15 +159,17 @@ sq_status sq_i8_gemm_i32(const int8_t* xq, const int8_t* wq, int32_t* acc, int64
 /* INT8 batched matmul of attention (Sec. 4): c[b] = round_to_16bit( fl32( float(a[b] B[b]) * alpha ) ).
  * a: device int8 [b, m, k]; bm: device int8, [b, n, k] if trans_b (Q K^T) else [b, k, n] (P V);
  * alpha: HOST scalar (e.g. Delta_Q Delta_K / sqrt(d), or Delta_V / 127);
- * c: device [b, m, n] of dtype `out`.  Batch strides in elements; k % 16 == 0; for trans_b == 0
- * also n % 16 == 0. */
+ * c: device [b, m, n] of dtype `out`.  Batch strides in elements (multiples of 16 for a and bm, of 8 for c);
+ * k % 16 == 0; for trans_b == 0 also n % 16 == 0; b <= 65535.  Needs no workspace at any shape. */
 sq_status sq_w8a8_bmm(const int8_t* a, const int8_t* bm, int trans_b, float alpha, void* c,
                       sq_dtype out, int64_t b, int64_t m, int64_t n, int64_t k, int64_t stride_a,
                       int64_t stride_b, int64_t stride_c, void* stream);
 
 /* Row softmax kept in 16-bit floating point (Sec. 4 keeps Softmax in FP16) followed by quantization
  * of the probabilities with the fixed step 1/127: pq = round(p * 127) in [0, 127].
- * s: device [rows, cols] 16-bit scores, packed; pq: device int8 [rows, cols]. */
+ * s: device [rows, cols] 16-bit scores, packed; pq: device int8 [rows, cols].
+ * Limits: cols % 8 == 0 (SQ_ERR_ALIGN), cols <= 16384 (SQ_ERR_UNSUPPORTED).  Scores of -inf (masked positions)
+ * get probability 0; a row that holds nothing but -inf gets codes 0 throughout.  NaN or +inf: unspecified. */
 sq_status sq_softmax_quant_p(const void* s, sq_dtype dtype, int64_t rows, int64_t cols, int8_t* pq,
                              void* stream);
 
@@ -170,7 +177,8 @@ sq_status sq_softmax_quant_p(const void* s, sq_dtype dtype, int64_t rows, int64_
  * beta_f = beta / s, folded offline as Sec. 4 describes) fused with per-token dynamic quantization:
  *   x_hat_tj = (x_tj - mean_t) * rstd_t * gamma_f_j + beta_f_j;  then Eq. 1 per token.
  * x: device [t, c_i] 16-bit packed; gamma_f, beta_f: device fp32 [c_i]; scale: device fp32 [t];
- * xq: device int8 [t, c_i] in layout `xq_layout`. */
+ * xq: device int8 [t, c_i] in layout `xq_layout`.
+ * Limits: c_i % 16 == 0 (SQ_ERR_ALIGN), c_i <= 16384 (SQ_ERR_UNSUPPORTED); gamma_f, beta_f 16-byte aligned. */
 sq_status sq_ln_quantize(const void* x, sq_dtype dtype, int64_t t, int64_t c_i, const float* gamma_f,
                          const float* beta_f, float eps, float* scale, int8_t* xq, sq_layout xq_layout,
                          void* stream);

@@ -195,10 +195,10 @@ void sq_strip_bmm_launch(const GemmArgs& a, int batch, bool bf16, hipStream_t st
     // Long strips: a three-deep ring and two workgroups per CU.  Short strips (the prologue weighs more): a
     // two-deep ring, three workgroups per CU.
     if (q.tiles_per_wg <= 6) {
-        if (bf16) hipLaunchKernelGGL((bmm_strip_kernel<true, 2, 4>), grid, dim3(320), 0, st, a, q);
-        else hipLaunchKernelGGL((bmm_strip_kernel<false, 2, 4>), grid, dim3(320), 0, st, a, q);
+        if (bf16) sq_launch((bmm_strip_kernel<true, 2, 4>), grid, dim3(320), 0, st, a, q);
+        else sq_launch((bmm_strip_kernel<false, 2, 4>), grid, dim3(320), 0, st, a, q);
     } else {
-        if (bf16) hipLaunchKernelGGL((bmm_strip_kernel<true, 3, 3>), grid, dim3(320), 0, st, a, q);
-        else hipLaunchKernelGGL((bmm_strip_kernel<false, 3, 3>), grid, dim3(320), 0, st, a, q);
+        if (bf16) sq_launch((bmm_strip_kernel<true, 3, 3>), grid, dim3(320), 0, st, a, q);
+        else sq_launch((bmm_strip_kernel<false, 3, 3>), grid, dim3(320), 0, st, a, q);
     }
 }

@@ -3,6 +3,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <tuple>
+#include <type_traits>
+
 #include "sqmi.h"
 
 typedef int v2i __attribute__((ext_vector_type(2)));
@@ -17,7 +20,16 @@ typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 // mode); bf16 is widened by a shift and narrowed with the integer nearest-even rule.
 SQ_DEVICE float f16_bits_to_f32(uint32_t h) { return (float)__builtin_bit_cast(_Float16, (uint16_t)h); }
 SQ_DEVICE float bf16_bits_to_f32(uint32_t b) { return __builtin_bit_cast(float, b << 16); }
-SQ_DEVICE uint32_t f32_to_f16_bits(float v) { return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)v); }
+// The narrowing is an opaque v_cvt_f16_f32: left to the compiler, a multiply or add that feeds a float -> half
+// conversion is merged into v_fma_mixlo_f16, which rounds the exact result once to fp16.  The arithmetic
+// fixed for the outputs is "round to fp32, then round to the 16-bit type"; the two differ whenever the fp32
+// rounding lands on an fp16 tie point (about one output in 2^13).
+SQ_DEVICE uint32_t f32_to_f16_bits(float v)
+{
+    uint32_t r;
+    asm("v_cvt_f16_f32 %0, %1" : "=v"(r) : "v"(v));
+    return r & 0xffffu;
+}
 SQ_DEVICE uint32_t f32_to_bf16_bits(float v)
 {
     uint32_t u = __builtin_bit_cast(uint32_t, v);
@@ -84,7 +96,30 @@ SQ_DEVICE float wave_sum(float v)
 
 // ---- host side
 static inline bool sq_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Launch bookkeeping of one entry point, per host thread.  Every kernel of the library is launched through
+// sq_launch, which keeps the status hipLaunchKernel itself returned for this launch (an error left behind by an
+// unrelated earlier HIP call of the application is neither reported as ours nor cleared) and launches nothing
+// more once a launch of the entry point has failed.  sq_launch_status closes the entry point: it returns that
+// status and resets it for the next call.
+inline thread_local hipError_t sq_tls_launch_error = hipSuccess;
+
+template <typename... P, typename... A>
+static inline void sq_launch(void (*kernel)(P...), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t st, A&&... args)
+{
+    static_assert(sizeof...(P) == sizeof...(A), "kernel argument count");
+    if (sq_tls_launch_error != hipSuccess) return;
+    std::tuple<std::decay_t<P>...> vals{static_cast<std::decay_t<P>>(args)...};
+    std::apply(
+        [&](auto&... v) {
+            void* argv[] = {(void*)&v...};
+            sq_tls_launch_error = hipLaunchKernel((const void*)kernel, grid, block, argv, lds_bytes, st);
+        },
+        vals);
+}
 static inline sq_status sq_launch_status()
 {
-    return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_HIP;
+    const hipError_t e = sq_tls_launch_error;
+    sq_tls_launch_error = hipSuccess;
+    return e == hipSuccess ? SQ_OK : SQ_ERR_HIP;
 }

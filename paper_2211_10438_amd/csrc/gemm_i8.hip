@@ -639,8 +639,8 @@ void launch_cfg(const Plan& pl, const GemmArgs& a, int batch, hipStream_t st, bo
     dim3 grid((unsigned)(pl.tiles_m * pl.tiles_n * pl.splits), (unsigned)batch);
 #define SQ_LAUNCH(BM, BN, WGM, WGN, NST)                                                                          \
     do {                                                                                                          \
-        if (tiled) hipLaunchKernelGGL((gemm_i8_kernel<BM, BN, WGM, WGN, NST, EPI, BF16, LAY_TILED>), grid, dim3(WGM * WGN * 64), 0, st, a); \
-        else hipLaunchKernelGGL((gemm_i8_kernel<BM, BN, WGM, WGN, NST, EPI, BF16, LAY_ROWS>), grid, dim3(WGM * WGN * 64), 0, st, a); \
+        if (tiled) sq_launch((gemm_i8_kernel<BM, BN, WGM, WGN, NST, EPI, BF16, LAY_TILED>), grid, dim3(WGM * WGN * 64), 0, st, a); \
+        else sq_launch((gemm_i8_kernel<BM, BN, WGM, WGN, NST, EPI, BF16, LAY_ROWS>), grid, dim3(WGM * WGN * 64), 0, st, a); \
     } while (0)
     switch (pl.cfg) {
         case 0: SQ_LAUNCH(256, 256, 2, 4, 4); break;
@@ -650,34 +650,38 @@ void launch_cfg(const Plan& pl, const GemmArgs& a, int batch, hipStream_t st, bo
         case 6: SQ_LAUNCH(256, 192, 4, 2, 4); break;
         case 9: SQ_LAUNCH(256, 384, 2, 4, 4); break;
         case 8:
-            if (tiled) hipLaunchKernelGGL((gemm_i8_kernel<128, 128, 2, 2, 3, EPI, BF16, LAY_TILED, 4, true>), grid, dim3(256), 0, st, a);
-            else hipLaunchKernelGGL((gemm_i8_kernel<128, 128, 2, 2, 3, EPI, BF16, LAY_ROWS, 4, true>), grid, dim3(256), 0, st, a);
+            if (tiled) sq_launch((gemm_i8_kernel<128, 128, 2, 2, 3, EPI, BF16, LAY_TILED, 4, true>), grid, dim3(256), 0, st, a);
+            else sq_launch((gemm_i8_kernel<128, 128, 2, 2, 3, EPI, BF16, LAY_ROWS, 4, true>), grid, dim3(256), 0, st, a);
             break;
         case 7:
-            if (tiled) hipLaunchKernelGGL((gemm_i8_kernel<128, 128, 2, 2, 3, EPI, BF16, LAY_TILED, 3>), grid, dim3(256), 0, st, a);
-            else hipLaunchKernelGGL((gemm_i8_kernel<128, 128, 2, 2, 3, EPI, BF16, LAY_ROWS, 3>), grid, dim3(256), 0, st, a);
+            if (tiled) sq_launch((gemm_i8_kernel<128, 128, 2, 2, 3, EPI, BF16, LAY_TILED, 3>), grid, dim3(256), 0, st, a);
+            else sq_launch((gemm_i8_kernel<128, 128, 2, 2, 3, EPI, BF16, LAY_ROWS, 3>), grid, dim3(256), 0, st, a);
             break;
         default:
             if constexpr (EPI == EPI_DEQUANT) {
-                hipLaunchKernelGGL((gemm_i8_kernel<256, 128, 4, 1, 5, EPI, BF16, LAY_BT>), grid, dim3(256), 0, st, a);
+                sq_launch((gemm_i8_kernel<256, 128, 4, 1, 5, EPI, BF16, LAY_BT>), grid, dim3(256), 0, st, a);
             }
             break;
     }
 #undef SQ_LAUNCH
 }
 
+// allow_split = false: the caller has no workspace to offer (sq_w8a8_bmm), so only plans that finish in one kernel
+// are considered.
 sq_status run_gemm(GemmArgs a, int64_t batch, bool to_i32, bool bf16, void* workspace, size_t ws_bytes, hipStream_t st,
-                   bool b_transposed = false, bool tiled = false)
+                   bool b_transposed = false, bool tiled = false, bool allow_split = true)
 {
     const int64_t total = (int64_t)a.M * a.N;
     auto reduce = [&](void* final_out) {  // a.acc_out = partials [a.splits][M][N]
         a.C = final_out;
         int blocks = (int)((total + 255) / 256);
         if (blocks > 4096) blocks = 4096;
-        if (bf16) hipLaunchKernelGGL(splitk_reduce_kernel<true>, dim3(blocks), dim3(256), 0, st, a, to_i32 ? 1 : 0);
-        else hipLaunchKernelGGL(splitk_reduce_kernel<false>, dim3(blocks), dim3(256), 0, st, a, to_i32 ? 1 : 0);
+        if (bf16) sq_launch(splitk_reduce_kernel<true>, dim3(blocks), dim3(256), 0, st, a, to_i32 ? 1 : 0);
+        else sq_launch(splitk_reduce_kernel<false>, dim3(blocks), dim3(256), 0, st, a, to_i32 ? 1 : 0);
     };
-    if (const int ss = b_transposed ? 0 : sq_stream_gemm_splits(a.M, a.N, a.K, batch)) {
+    int ss = b_transposed ? 0 : sq_stream_gemm_splits(a.M, a.N, a.K, batch);
+    if (ss > 1 && !allow_split) ss = 0;  // the streaming plan wants a K split: leave the shape to the tile kernels
+    if (ss) {
         // few tokens, wide C_o: stream W once through one workgroup per CU
         if (ss > 1) {
             const size_t need = (size_t)ss * total * sizeof(int32_t);
@@ -692,7 +696,7 @@ sq_status run_gemm(GemmArgs a, int64_t batch, bool to_i32, bool bf16, void* work
         }
         return sq_launch_status();
     }
-    Plan pl = make_plan(a.M, a.N, a.K, batch, true, b_transposed);
+    Plan pl = make_plan(a.M, a.N, a.K, batch, allow_split, b_transposed);
     a.tiles_m = pl.tiles_m;
     a.tiles_n = pl.tiles_n;
     a.splits = pl.splits;
@@ -818,7 +822,7 @@ sq_status sq_internal_bmm(const int8_t* a_, const int8_t* b_, int trans_b, float
         sq_strip_bmm_launch(a, (int)batch, out == SQ_BF16, (hipStream_t)stream);
         return sq_launch_status();
     }
-    return run_gemm(a, batch, false, out == SQ_BF16, nullptr, 0, (hipStream_t)stream, !trans_b);
+    return run_gemm(a, batch, false, out == SQ_BF16, nullptr, 0, (hipStream_t)stream, !trans_b, false, false);
 }
 
 }  // extern "C"

@@ -315,12 +315,12 @@ void sq_stream_gemm_launch(const GemmArgs& a, bool to_i32, bool bf16, bool tiled
     q.bf16 = bf16 ? 1 : 0;
     const dim3 grid((unsigned)(q.gn * q.gk)), block(256), block8(512);
     switch (q.na * 2 + q.nt_w) {
-        case 2: hipLaunchKernelGGL((gemm_i8_stream_kernel<1, 1, 4, 4, false>), grid, block, 0, st, a, q); break;
-        case 3: hipLaunchKernelGGL((gemm_i8_stream_kernel<1, 1, 4, 4, true>), grid, block, 0, st, a, q); break;
-        case 4: hipLaunchKernelGGL((gemm_i8_stream_kernel<1, 2, 8, 4, false>), grid, block, 0, st, a, q); break;
-        case 5: hipLaunchKernelGGL((gemm_i8_stream_kernel<1, 2, 8, 4, true>), grid, block, 0, st, a, q); break;
-        case 8: hipLaunchKernelGGL((gemm_i8_stream_kernel<1, 4, 8, 8, false>), grid, block8, 0, st, a, q); break;
-        case 9: hipLaunchKernelGGL((gemm_i8_stream_kernel<1, 4, 8, 8, true>), grid, block8, 0, st, a, q); break;
-        default: hipLaunchKernelGGL((gemm_i8_stream_kernel<2, 4, 12, 8, false>), grid, block8, 0, st, a, q); break;
+        case 2: sq_launch((gemm_i8_stream_kernel<1, 1, 4, 4, false>), grid, block, 0, st, a, q); break;
+        case 3: sq_launch((gemm_i8_stream_kernel<1, 1, 4, 4, true>), grid, block, 0, st, a, q); break;
+        case 4: sq_launch((gemm_i8_stream_kernel<1, 2, 8, 4, false>), grid, block, 0, st, a, q); break;
+        case 5: sq_launch((gemm_i8_stream_kernel<1, 2, 8, 4, true>), grid, block, 0, st, a, q); break;
+        case 8: sq_launch((gemm_i8_stream_kernel<1, 4, 8, 8, false>), grid, block8, 0, st, a, q); break;
+        case 9: sq_launch((gemm_i8_stream_kernel<1, 4, 8, 8, true>), grid, block8, 0, st, a, q); break;
+        default: sq_launch((gemm_i8_stream_kernel<2, 4, 12, 8, false>), grid, block8, 0, st, a, q); break;
     }
 }

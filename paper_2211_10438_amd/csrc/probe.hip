@@ -50,7 +50,7 @@ sq_status sq_probe_mfma_i8(const int8_t* data, size_t data_bytes, int workgroups
     if (workgroups <= 0 || workgroups > 65535 || iters <= 0) return SQ_ERR_SHAPE;
     if (data_bytes < (size_t)workgroups * 8 * 6 * 64 * 16) return SQ_ERR_WORKSPACE;
     if (!sq_aligned16(data) || !sq_aligned16(sink)) return SQ_ERR_ALIGN;
-    hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)workgroups), dim3(512), 0, (hipStream_t)stream, (const v4i*)data, iters, sink);
+    sq_launch(mfma_probe_kernel, dim3((unsigned)workgroups), dim3(512), 0, (hipStream_t)stream, (const v4i*)data, iters, sink);
     return sq_launch_status();
 }
 

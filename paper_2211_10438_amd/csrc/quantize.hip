@@ -264,11 +264,11 @@ void launch_per_token(const uint16_t* x, int64_t ldx, int c_i, int64_t t, const 
                       bool tiled, hipStream_t st)
 {
     const int nvec = c_i >> 3;
-#define SQ_WAVE(NV) hipLaunchKernelGGL((quant_per_token_wave<BF16, NV>), dim3((unsigned)((t + 3) / 4)), dim3(256), 0, st, x, ldx, c_i, t, inv_s, scale, xq, tiled)
+#define SQ_WAVE(NV) sq_launch((quant_per_token_wave<BF16, NV>), dim3((unsigned)((t + 3) / 4)), dim3(256), 0, st, x, ldx, c_i, t, inv_s, scale, xq, tiled)
 #define SQ_BLOCK(NV, NT)                                                                                                        \
     do {                                                                                                                        \
-        if (inv_s && NV <= 8) hipLaunchKernelGGL((quant_per_token_block<BF16, NV, NT, true>), dim3((unsigned)t), dim3(NT), 0, st, x, ldx, c_i, inv_s, scale, xq, tiled); \
-        else hipLaunchKernelGGL((quant_per_token_block<BF16, NV, NT, false>), dim3((unsigned)t), dim3(NT), 0, st, x, ldx, c_i, inv_s, scale, xq, tiled);                 \
+        if (inv_s && NV <= 8) sq_launch((quant_per_token_block<BF16, NV, NT, true>), dim3((unsigned)t), dim3(NT), 0, st, x, ldx, c_i, inv_s, scale, xq, tiled); \
+        else sq_launch((quant_per_token_block<BF16, NV, NT, false>), dim3((unsigned)t), dim3(NT), 0, st, x, ldx, c_i, inv_s, scale, xq, tiled);                 \
     } while (0)
     if (nvec <= 64) SQ_WAVE(1);
     else if (nvec <= 128) SQ_WAVE(2);
@@ -279,7 +279,7 @@ void launch_per_token(const uint16_t* x, int64_t ldx, int c_i, int64_t t, const 
     else if (nvec <= 4096) SQ_BLOCK(4, 1024);
     else if (nvec <= 6144) SQ_BLOCK(6, 1024);
     else if (nvec <= 8192) SQ_BLOCK(8, 1024);
-    else hipLaunchKernelGGL((quant_per_token_stream<BF16>), dim3((unsigned)t), dim3(256), 0, st, x, ldx, c_i, inv_s, scale, xq, tiled);
+    else sq_launch((quant_per_token_stream<BF16>), dim3((unsigned)t), dim3(256), 0, st, x, ldx, c_i, inv_s, scale, xq, tiled);
 #undef SQ_WAVE
 #undef SQ_BLOCK
 }
@@ -321,17 +321,17 @@ sq_status sq_quantize_act(const void* x, sq_dtype dtype, int64_t t, int64_t c_i,
     const int grid = grid_for(t * (c_i >> 3));
     if (mode == SQ_PER_TENSOR_DYNAMIC) {
         uint32_t* amax = (uint32_t*)workspace;
-        hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, st, amax, 0u, 1);
+        sq_launch(fill_u32_kernel, dim3(1), dim3(64), 0, st, amax, 0u, 1);
         if (bf) {
-            hipLaunchKernelGGL(tensor_absmax_kernel<true>, dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, amax);
-            hipLaunchKernelGGL((quant_per_tensor_kernel<true, true>), dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, amax, xq, tiled);
+            sq_launch(tensor_absmax_kernel<true>, dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, amax);
+            sq_launch((quant_per_tensor_kernel<true, true>), dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, amax, xq, tiled);
         } else {
-            hipLaunchKernelGGL(tensor_absmax_kernel<false>, dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, amax);
-            hipLaunchKernelGGL((quant_per_tensor_kernel<false, true>), dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, amax, xq, tiled);
+            sq_launch(tensor_absmax_kernel<false>, dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, amax);
+            sq_launch((quant_per_tensor_kernel<false, true>), dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, amax, xq, tiled);
         }
     } else {
-        if (bf) hipLaunchKernelGGL((quant_per_tensor_kernel<true, false>), dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, (const uint32_t*)nullptr, xq, tiled);
-        else hipLaunchKernelGGL((quant_per_tensor_kernel<false, false>), dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, (const uint32_t*)nullptr, xq, tiled);
+        if (bf) sq_launch((quant_per_tensor_kernel<true, false>), dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, (const uint32_t*)nullptr, xq, tiled);
+        else sq_launch((quant_per_tensor_kernel<false, false>), dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, (const uint32_t*)nullptr, xq, tiled);
     }
     return sq_launch_status();
 }
@@ -343,13 +343,13 @@ sq_status sq_act_absmax_per_channel(const void* x, sq_dtype dtype, int64_t t, in
     if (dtype != SQ_F16 && dtype != SQ_BF16) return SQ_ERR_UNSUPPORTED;
     if ((c_i & 15) || !sq_aligned16(x) || !sq_aligned16(out)) return SQ_ERR_ALIGN;
     hipStream_t st = (hipStream_t)stream;
-    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((c_i + 255) / 256)), dim3(256), 0, st, (uint32_t*)out, 0u, (int)c_i);
+    sq_launch(fill_u32_kernel, dim3((unsigned)((c_i + 255) / 256)), dim3(256), 0, st, (uint32_t*)out, 0u, (int)c_i);
     const int nvec = (int)(c_i >> 3);
     dim3 grid((unsigned)((nvec + 255) / 256), (unsigned)(t < 256 ? t : 256));
     if (dtype == SQ_BF16)
-        hipLaunchKernelGGL(act_absmax_per_channel_kernel<true>, grid, dim3(256), 0, st, (const uint16_t*)x, (int)c_i, t, (uint32_t*)out);
+        sq_launch(act_absmax_per_channel_kernel<true>, grid, dim3(256), 0, st, (const uint16_t*)x, (int)c_i, t, (uint32_t*)out);
     else
-        hipLaunchKernelGGL(act_absmax_per_channel_kernel<false>, grid, dim3(256), 0, st, (const uint16_t*)x, (int)c_i, t, (uint32_t*)out);
+        sq_launch(act_absmax_per_channel_kernel<false>, grid, dim3(256), 0, st, (const uint16_t*)x, (int)c_i, t, (uint32_t*)out);
     return sq_launch_status();
 }
 

@@ -77,7 +77,8 @@ __global__ __launch_bounds__(256) void softmax_quant_kernel(const uint16_t* __re
         }
     }
     mx = block_max_r(mx, red);
-    const float nmx = -mx * 1.44269504088896340736f;
+    // a row of -inf only (fully masked) has no maximum to shift by: its exponentials are 0 and so are its codes
+    const float nmx = mx == -__builtin_inff() ? 0.0f : -mx * 1.44269504088896340736f;
     float sum = 0.0f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
@@ -91,7 +92,7 @@ __global__ __launch_bounds__(256) void softmax_quant_kernel(const uint16_t* __re
         }
     }
     sum = block_sum_r(sum, red);
-    const float inv = 1.0f / sum;
+    const float inv = sum > 0.0f ? 1.0f / sum : 0.0f;
     v2u* out = (v2u*)(pq + row * (int64_t)cols);
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
@@ -133,7 +134,8 @@ __global__ __launch_bounds__(256) void softmax_quant_wave_kernel(const uint16_t*
         }
     }
     mx = wave_max(mx);
-    const float nmx = -mx * 1.44269504088896340736f;
+    // a row of -inf only (fully masked) has no maximum to shift by: its exponentials are 0 and so are its codes
+    const float nmx = mx == -__builtin_inff() ? 0.0f : -mx * 1.44269504088896340736f;
     float sum = 0.0f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
@@ -147,7 +149,7 @@ __global__ __launch_bounds__(256) void softmax_quant_wave_kernel(const uint16_t*
         }
     }
     sum = wave_sum(sum);
-    const float inv = 1.0f / sum;
+    const float inv = sum > 0.0f ? 1.0f / sum : 0.0f;
     v2u* out = (v2u*)(pq + row * (int64_t)cols);
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
@@ -313,8 +315,8 @@ sq_status sq_softmax_quant_p(const void* s, sq_dtype dtype, int64_t rows, int64_
     hipStream_t st = (hipStream_t)stream;
     const int nvec = (int)(cols >> 3);
     const uint16_t* sp = (const uint16_t*)s;
-#define SQ_SM(BF, NV) hipLaunchKernelGGL((softmax_quant_kernel<BF, NV>), dim3((unsigned)rows), dim3(256), 0, st, sp, (int)cols, pq)
-#define SQ_SMW(BF, NV) hipLaunchKernelGGL((softmax_quant_wave_kernel<BF, NV>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, sp, rows, (int)cols, pq)
+#define SQ_SM(BF, NV) sq_launch((softmax_quant_kernel<BF, NV>), dim3((unsigned)rows), dim3(256), 0, st, sp, (int)cols, pq)
+#define SQ_SMW(BF, NV) sq_launch((softmax_quant_wave_kernel<BF, NV>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, sp, rows, (int)cols, pq)
     if (dtype == SQ_BF16) {
         if (nvec <= 64) SQ_SMW(true, 1); else if (nvec <= 128) SQ_SMW(true, 2); else if (nvec <= 256) SQ_SMW(true, 4);
         else if (nvec <= 512) SQ_SMW(true, 8); else if (nvec <= 1024) SQ_SM(true, 4); else SQ_SM(true, 8);
@@ -344,8 +346,8 @@ sq_status sq_ln_quantize(const void* x, sq_dtype dtype, int64_t t, int64_t c_i, 
     const uint16_t* xp = (const uint16_t*)x;
     // Measured choice: up to 2048 channels one row per wave; up to 8192 one row per 256-thread workgroup; wider rows
     // one row per 512-thread workgroup (more loads in flight per row, fewer registers per thread).
-#define SQ_LN(BF, NV, NT) hipLaunchKernelGGL((ln_quant_kernel<BF, NV, NT>), dim3((unsigned)t), dim3(NT), 0, st, xp, (int)c_i, gamma_f, beta_f, eps, scale, xq, tiled)
-#define SQ_LNW(BF, NV) hipLaunchKernelGGL((ln_quant_wave_kernel<BF, NV>), dim3((unsigned)((t + 3) / 4)), dim3(256), 0, st, xp, t, (int)c_i, gamma_f, beta_f, eps, scale, xq, tiled)
+#define SQ_LN(BF, NV, NT) sq_launch((ln_quant_kernel<BF, NV, NT>), dim3((unsigned)t), dim3(NT), 0, st, xp, (int)c_i, gamma_f, beta_f, eps, scale, xq, tiled)
+#define SQ_LNW(BF, NV) sq_launch((ln_quant_wave_kernel<BF, NV>), dim3((unsigned)((t + 3) / 4)), dim3(256), 0, st, xp, t, (int)c_i, gamma_f, beta_f, eps, scale, xq, tiled)
     if (dtype == SQ_BF16) {
         if (nvec <= 128) SQ_LNW(true, 2); else if (nvec <= 256) SQ_LNW(true, 4); else if (nvec <= 512) SQ_LN(true, 2, 256);
         else if (nvec <= 1024) SQ_LN(true, 4, 256); else if (nvec <= 1536) SQ_LN(true, 3, 512); else SQ_LN(true, 4, 512);

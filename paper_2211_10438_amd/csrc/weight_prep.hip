@@ -138,9 +138,9 @@ sq_status sq_weight_absmax_per_in_channel(const void* w, sq_dtype dtype, int64_t
     if ((c_o & 7) || !sq_aligned16(w)) return SQ_ERR_ALIGN;
     const unsigned grid = (unsigned)(c_i < 65535 ? c_i : 65535);
     if (dtype == SQ_BF16)
-        hipLaunchKernelGGL(weight_row_absmax_kernel<true>, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const uint16_t*)w, (int)c_i, (int)c_o, (const float*)nullptr, out, (uint32_t*)nullptr);
+        sq_launch(weight_row_absmax_kernel<true>, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const uint16_t*)w, (int)c_i, (int)c_o, (const float*)nullptr, out, (uint32_t*)nullptr);
     else
-        hipLaunchKernelGGL(weight_row_absmax_kernel<false>, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const uint16_t*)w, (int)c_i, (int)c_o, (const float*)nullptr, out, (uint32_t*)nullptr);
+        sq_launch(weight_row_absmax_kernel<false>, dim3(grid), dim3(256), 0, (hipStream_t)stream, (const uint16_t*)w, (int)c_i, (int)c_o, (const float*)nullptr, out, (uint32_t*)nullptr);
     return sq_launch_status();
 }
 
@@ -161,18 +161,18 @@ sq_status sq_prepare_weight(const void* w, sq_dtype dtype, const float* s, int64
     hipStream_t st = (hipStream_t)stream;
     uint32_t* amax = (uint32_t*)workspace;
     const int64_t ncell = pc ? c_o : 1;
-    hipLaunchKernelGGL(zero_u32_kernel, dim3((unsigned)((ncell + 255) / 256 < 1024 ? (ncell + 255) / 256 : 1024)), dim3(256), 0, st, amax, ncell);
+    sq_launch(zero_u32_kernel, dim3((unsigned)((ncell + 255) / 256 < 1024 ? (ncell + 255) / 256 : 1024)), dim3(256), 0, st, amax, ncell);
     const unsigned grid1 = (unsigned)(c_i < 4096 ? c_i : 4096);
     dim3 gridc((unsigned)((c_o / 8 + 255) / 256), (unsigned)((c_i + 63) / 64));
     dim3 grid2((unsigned)((c_o + 63) / 64), (unsigned)((c_i + 63) / 64));
     if (dtype == SQ_BF16) {
-        if (pc) hipLaunchKernelGGL(weight_col_absmax_kernel<true>, gridc, dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, amax);
-        else hipLaunchKernelGGL(weight_row_absmax_kernel<true>, dim3(grid1), dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, (float*)nullptr, amax);
-        hipLaunchKernelGGL(weight_quant_transpose_kernel<true>, grid2, dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, amax, w_scale, wq, tiled, pc);
+        if (pc) sq_launch(weight_col_absmax_kernel<true>, gridc, dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, amax);
+        else sq_launch(weight_row_absmax_kernel<true>, dim3(grid1), dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, (float*)nullptr, amax);
+        sq_launch(weight_quant_transpose_kernel<true>, grid2, dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, amax, w_scale, wq, tiled, pc);
     } else {
-        if (pc) hipLaunchKernelGGL(weight_col_absmax_kernel<false>, gridc, dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, amax);
-        else hipLaunchKernelGGL(weight_row_absmax_kernel<false>, dim3(grid1), dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, (float*)nullptr, amax);
-        hipLaunchKernelGGL(weight_quant_transpose_kernel<false>, grid2, dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, amax, w_scale, wq, tiled, pc);
+        if (pc) sq_launch(weight_col_absmax_kernel<false>, gridc, dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, amax);
+        else sq_launch(weight_row_absmax_kernel<false>, dim3(grid1), dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, (float*)nullptr, amax);
+        sq_launch(weight_quant_transpose_kernel<false>, grid2, dim3(256), 0, st, (const uint16_t*)w, (int)c_i, (int)c_o, s, amax, w_scale, wq, tiled, pc);
     }
     return sq_launch_status();
 }

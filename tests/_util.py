@@ -32,6 +32,14 @@ def ulp_distance(a_bits: np.ndarray, b_bits: np.ndarray) -> np.ndarray:
     return np.abs(ordered(a_bits) - ordered(b_bits))
 
 
+def assert_identical_16(d: np.ndarray, what: str = ""):
+    """Gate for the dequantizing epilogues (Eq. 2 outer scaling): a fixed sequence of IEEE fp32 operations without
+    contraction on both sides, so the 16-bit outputs must be identical; 1 ulp is the hard limit of the contract
+    and is reported separately so that a failure says which of the two was broken."""
+    assert d.max() <= 1, f"{what} max ulp distance {d.max()} (contract: <= 1)"
+    assert d.max() == 0, f"{what} {int((d != 0).sum())} of {d.size} outputs differ by 1 ulp (expected identical)"
+
+
 def random_bf16_bits(shape, seed, scale=1.0):
     rng = np.random.default_rng(seed)
     f = (rng.standard_normal(shape, dtype=np.float32) * np.float32(scale))
@@ -54,11 +62,19 @@ def tiled_index(rows: int, k: int) -> np.ndarray:
 
 
 def tiled_to_rows(t: torch.Tensor) -> np.ndarray:
-    """Logical [rows, k] codes of a tensor returned by the binding in TILED layout."""
+    """Logical [rows, k] codes of a tensor returned by the binding in TILED layout.  Block-wise inverse of
+    rows_to_tiled_dev (reshapes instead of a gather through tiled_index, which would need an int64 index per
+    byte: too much for a 600 MB weight)."""
     rows, k = t.shape
     base = t._base if t._base is not None else t
     raw = base.cpu().numpy().reshape(-1)
-    return raw[tiled_index(rows, k)]
+    pad = (rows + 15) // 16 * 16
+    blk = raw[:pad * k].reshape(pad // 16, k // 64, 16, 4, 16)  # [R/16, K/64, row, stored position, byte]
+    rr = np.arange(16)
+    sw = ((rr >> 1) & 3) ^ ((rr >> 3) & 1)
+    pos_of_chunk = np.arange(4)[None, :] ^ sw[:, None]  # chunk c of row r is stored at position c ^ sw(r)
+    out = blk[:, :, rr[:, None], pos_of_chunk, :]  # [R/16, K/64, row, chunk, byte]
+    return np.ascontiguousarray(out.transpose(0, 2, 1, 3, 4)).reshape(pad, k)[:rows]
 
 
 def rows_to_tiled_dev(codes: np.ndarray) -> torch.Tensor:

@@ -96,3 +96,49 @@ def test_argument_validation_happens_before_any_launch():
     assert L.sq_ln_quantize(fake, 0, 4, 64, NULL, fake, 1e-5, fake, fake, 0, NULL) == 1
     assert L.sq_tiled_bytes(33, 128) == 48 * 128 and L.sq_tiled_bytes(33, 100) == 0
     assert L.sq_workspace_bytes(sq.OP_W8A8_LINEAR, 2048, 12288, 36864) == 0 or True
+
+
+def test_documented_limits_are_enforced_on_the_host():
+    """Limits the header states per entry point (beyond 16-byte alignment and c_i % 16)."""
+    L = sq.lib()
+    fake = ctypes.c_void_p(0x1000)
+    NULL = None
+    assert L.sq_weight_absmax_per_in_channel(fake, 0, 64, 60, fake, NULL) == 3            # c_o % 8
+    assert L.sq_prepare_weight(fake, 0, NULL, 64, 60, fake, 0, fake, 0, fake, 1 << 20, NULL) == 3   # c_o % 8
+    assert L.sq_prepare_weight(fake, 0, NULL, 64 * 65536, 8, fake, 0, fake, 0, fake, 1 << 20, NULL) == 2  # c_i > 64 * 65535
+    assert L.sq_softmax_quant_p(fake, 0, 4, 16392, fake, NULL) == 4                       # cols > 16384
+    assert L.sq_softmax_quant_p(fake, 0, 4, 20, fake, NULL) == 3                          # cols % 8
+    assert L.sq_ln_quantize(fake, 0, 4, 16400, fake, fake, 1e-5, fake, fake, 0, NULL) == 4  # c_i > 16384
+    assert L.sq_ln_quantize(fake, 0, 4, 72, fake, fake, 1e-5, fake, fake, 0, NULL) == 3    # c_i % 16
+    assert L.sq_w8a8_bmm(fake, fake, 0, 1.0, fake, 0, 2, 16, 24, 16, 256, 384, 384, NULL) == 3  # P V: n % 16
+    assert L.sq_w8a8_bmm(fake, fake, 1, 1.0, fake, 0, 70000, 16, 16, 16, 256, 256, 256, NULL) == 2  # b > 65535
+
+
+def test_bmm_never_asks_for_a_workspace():
+    """sq_w8a8_bmm has no workspace argument, so no shape may fail for want of one: batch 1 with a long contraction
+    (where the linear layer's planner would split K) must reach the launch.  Run where no GPU is present, the launch
+    itself then fails with SQ_ERR_HIP; the point is that the status is not SQ_ERR_WORKSPACE."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("fake pointers must never reach a real GPU")
+    L = sq.lib()
+    fake = ctypes.c_void_p(0x1000)
+    for b, m, n, k in [(1, 64, 512, 2048), (1, 512, 512, 4096), (1, 16, 256, 1024), (1, 128, 8192, 4096)]:
+        assert L.sq_workspace_bytes(sq.OP_W8A8_BMM, m, k, n) == 0
+        st = L.sq_w8a8_bmm(fake, fake, 1, 1.0, fake, 0, b, m, n, k, m * k, n * k, m * n, None)
+        assert st != 5, (b, m, n, k)
+
+
+def test_tiled_layout_plumbing_of_the_tests_is_self_consistent():
+    """tests/_util.py converts between row order and the TILED layout two ways (a gather through the header's offset
+    formula, and block reshapes for large operands): both must agree, or the TILED parity tests compare garbage."""
+    import torch
+    from tests import _util as u
+    rng = np.random.default_rng(0)
+    for rows, k in [(37, 192), (16, 64), (130, 256)]:
+        codes = rng.integers(-127, 128, (rows, k), dtype=np.int8)
+        pad = (rows + 15) // 16 * 16
+        raw = np.zeros(pad * k, np.int8)
+        raw[u.tiled_index(rows, k).reshape(-1)] = codes.reshape(-1)
+        t = torch.from_numpy(raw.reshape(pad, k))[:rows]
+        assert np.array_equal(u.tiled_to_rows(t), codes)

@@ -9,7 +9,7 @@ import pytest
 import oracle
 from paper_2211_10438_amd import binding as sq
 from paper_2211_10438_amd import synth
-from tests._util import BF16, F16, bits_from_dev, dev, torch_dtype, ulp_distance
+from tests._util import assert_identical_16, BF16, F16, bits_from_dev, dev, torch_dtype, ulp_distance
 
 pytestmark = pytest.mark.gpu
 
@@ -35,7 +35,7 @@ def test_strip_scores_parity(b, m, n, k, odt):
     ref = oracle.w8a8_bmm(a, bt, True, alpha, odt)
     c = sq.w8a8_bmm(dev(a), dev(bt), True, alpha, torch_dtype(odt))
     d = ulp_distance(bits_from_dev(c), ref)
-    assert d.max() <= 1 and (d == 0).mean() > 0.999
+    assert_identical_16(d)
 
 
 def test_strip_scores_saturated_codes_and_untouched_neighbours():

@@ -1,5 +1,7 @@
-"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration
-bench.py times.  Where the oracle cannot afford every output it computes a seeded sample of rows /
+"""GPU parity at the full sizes of the benchmark configurations.  The OPT-175B linears (configuration 3, the
+workload bench.py times) run in both operand layouts: TILED is the launch configuration bench.py times (weights
+prepared TILED on the GPU, activations quantized TILED, the TILED instantiations of the GEMM kernels), ROW_MAJOR
+the default of the C ABI.  Where the oracle cannot afford every output it computes a seeded sample of rows /
 heads one by one, and integer checksums that cover every output (sum over tokens of the int32
 accumulators equals (sum of activation codes) x weight codes, exactly)."""
 import numpy as np
@@ -9,7 +11,7 @@ import torch
 import oracle
 from paper_2211_10438_amd import binding as sq
 from paper_2211_10438_amd import synth
-from tests._util import BF16, F16, bits_from_dev, dev, to_dev_16, ulp_distance
+from tests._util import BF16, F16, assert_identical_16, bits_from_dev, dev, tiled_to_rows, to_dev_16, ulp_distance
 
 pytestmark = pytest.mark.gpu
 
@@ -73,7 +75,7 @@ def test_config2_opt13b_ffn_pair():
     y1 = sq.w8a8_linear(xq, xs, wq1, ws1, torch.float16, relu=True)
     y1_ref = oracle.w8a8_linear(xq_ref, xs_ref, wq1_ref, ws1_ref, F16, relu=True)
     d = ulp_distance(bits_from_dev(y1), y1_ref)
-    assert d.max() <= 1 and (d == 0).mean() > 0.999
+    assert_identical_16(d)
     acc = sq.i8_gemm_i32(xq, wq1).cpu().numpy()
     assert np.array_equal(acc, oracle.i8_gemm_i32(xq_ref, wq1_ref))
     # FC2 on the real ReLU output (s = 1)
@@ -88,16 +90,19 @@ def test_config2_opt13b_ffn_pair():
     y2 = sq.w8a8_linear(xq2, xs2, wq2, ws2, torch.float16)
     y2_ref = oracle.w8a8_linear(xq2_ref, xs2_ref, wq2_ref, ws2_ref, F16)
     d = ulp_distance(bits_from_dev(y2), y2_ref)
-    assert d.max() <= 1 and (d == 0).mean() > 0.999
+    assert_identical_16(d)
 
 
 OPT175B = [(l.name, l.c_i, l.c_o) for l in synth.OPT175B_LINEARS]
 
 
+@pytest.mark.parametrize("layout", [sq.TILED, sq.ROW_MAJOR], ids=["tiled", "rows"])
 @pytest.mark.parametrize("name,c_i,c_o", OPT175B)
-def test_config3_opt175b_linears(name, c_i, c_o):
-    """All token counts of the configuration for one layer shape; bf16 out, per-token dynamic."""
-    _progress(f"config 3: {name} {c_i} -> {c_o}: generating inputs")
+def test_config3_opt175b_linears(name, c_i, c_o, layout):
+    """All token counts of the configuration for one layer shape; bf16 out, per-token dynamic.  In the TILED layout the
+    GPU's code tensors are brought back to row order (index plumbing only) before they are compared with the oracle's."""
+    _progress(f"config 3: {name} {c_i} -> {c_o} layout={layout}: generating inputs")
+    codes_of = tiled_to_rows if layout == sq.TILED else (lambda tns: tns.cpu().numpy())
     idx = [n for n, _, _ in OPT175B].index(name)
     smoothed = name in ("qkv", "fc1")
     n_out = synth.n_outlier_channels(c_i, 0.005)
@@ -112,24 +117,24 @@ def test_config3_opt175b_linears(name, c_i, c_o):
     wd = to_dev_16(w, F16)
     if smoothed:
         assert np.array_equal(sq.weight_absmax_per_in_channel(wd).cpu().numpy(), oracle.weight_absmax_per_in_channel(w, F16))
-    wq, ws = sq.prepare_weight(wd, None if s is None else dev(s))
+    wq, ws = sq.prepare_weight(wd, None if s is None else dev(s), layout=layout)
     del wd, w
     assert ws.item() == ws_ref[0]
-    assert torch.equal(wq.cpu(), torch.from_numpy(wq_ref)), "weight codes differ"
+    assert np.array_equal(codes_of(wq), wq_ref), "weight codes differ"
     inv_s_d = None if inv_s is None else dev(inv_s)
     for m in synth.OPT175B_TOKENS:
         _progress(f"config 3: {name} M={m}")
         x = synth.activations(m, c_i, ch, 80.0, synth.BASE_SEED + 60 + idx + m)
         xq_ref, xs_ref = oracle.quantize_act(x, F16, oracle.PER_TOKEN_DYNAMIC, inv_s=inv_s)
-        xq, xs = sq.quantize_act(to_dev_16(x, F16), sq.PER_TOKEN_DYNAMIC, inv_s=inv_s_d)
-        assert np.array_equal(xq.cpu().numpy(), xq_ref) and np.array_equal(xs.cpu().numpy(), xs_ref)
-        y = sq.w8a8_linear(xq, xs, wq, ws, torch.bfloat16)
+        xq, xs = sq.quantize_act(to_dev_16(x, F16), sq.PER_TOKEN_DYNAMIC, inv_s=inv_s_d, layout=layout)
+        assert np.array_equal(codes_of(xq), xq_ref) and np.array_equal(xs.cpu().numpy(), xs_ref)
+        y = sq.w8a8_linear(xq, xs, wq, ws, torch.bfloat16, layout=layout)
         rows = _sample_rows(m, 40 if m > 128 else m, 70 + idx + m)
         y_ref = oracle.w8a8_linear(xq_ref, xs_ref, wq_ref, ws_ref, BF16, rows=rows)
         d = ulp_distance(bits_from_dev(y[torch.from_numpy(rows).cuda()]), y_ref[rows])
-        assert d.max() <= 1 and (d == 0).mean() > 0.999, f"M={m}: max ulp {d.max()}"
+        assert_identical_16(d)
         # every accumulator is covered by the exact column checksum
-        acc = sq.i8_gemm_i32(xq, wq)
+        acc = sq.i8_gemm_i32(xq, wq, layout=layout)
         got = acc.sum(dim=0, dtype=torch.int64).cpu().numpy().astype(np.float64)
         assert np.array_equal(got, _column_checksum(xq_ref, wq_ref)), f"M={m}: column checksum differs"
         del acc, y
@@ -214,13 +219,13 @@ def test_config5_opt66b_decoder_layer_chain():
         ref = oracle.w8a8_linear(xq.cpu().numpy(), xs.cpu().numpy(), wq.cpu().numpy(), ws.cpu().numpy(), F16,
                                  bias=bias, residual_bits=None if res is None else bits_from_dev(res), relu=relu, rows=rows)
         dd = ulp_distance(bits_from_dev(y[torch.from_numpy(rows).cuda()]), ref[rows])
-        assert dd.max() <= 1 and (dd == 0).mean() > 0.999, f"{name}: max ulp {dd.max()}"
+        assert_identical_16(dd)
 
     def check_ln(name, x16, gamma_f, beta_f, xq, xs, seed):
         rows = _sample_rows(t, 8, seed)
         q_ref, s_ref = oracle.ln_quantize(bits_from_dev(x16[torch.from_numpy(rows).cuda()]), F16, gamma_f, beta_f)
         q = xq[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.int32)
-        assert np.abs(q - q_ref.astype(np.int32)).max() <= 1 and (q != q_ref).mean() <= 2e-3, name
+        assert np.abs(q - q_ref.astype(np.int32)).max() <= 1 and (q != q_ref).mean() <= 1e-3, name
         assert np.allclose(xs[torch.from_numpy(rows).cuda()].cpu().numpy(), s_ref, rtol=1e-5), name
 
     def check_quant(name, x16, xq, xs, seed):

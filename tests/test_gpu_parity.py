@@ -8,7 +8,7 @@ import torch
 import oracle
 from paper_2211_10438_amd import binding as sq
 from paper_2211_10438_amd import synth
-from tests._util import (BF16, F16, bits_from_dev, dev, random_bf16_bits, to_dev_16, torch_dtype, ulp_distance)
+from tests._util import (assert_identical_16, BF16, F16, bits_from_dev, dev, random_bf16_bits, to_dev_16, torch_dtype, ulp_distance)
 
 pytestmark = pytest.mark.gpu
 
@@ -141,8 +141,7 @@ def test_w8a8_linear_parity(t, c_i, c_o, odt, per_token, use_bias, relu, use_res
     y = sq.w8a8_linear(dev(xq), dev(xs), dev(wq), dev(ws), torch_dtype(odt), bias=None if bias is None else dev(bias),
                        residual=None if res is None else to_dev_16(res, odt), relu=relu)
     d = ulp_distance(bits_from_dev(y), ref)
-    assert d.max() <= 1, f"max ulp distance {d.max()}"
-    assert (d == 0).mean() > 0.999
+    assert_identical_16(d)
 
 
 # ------------------------------------------------------------------ offline preparation
@@ -179,7 +178,10 @@ def test_calibration_statistics_and_smooth_scales():
 
 # ------------------------------------------------------------------ attention BMMs + glue
 
-BMM_CASES = [(1, 16, 16, 16), (3, 100, 72, 128), (5, 300, 260, 128), (2, 512, 512, 64), (7, 33, 1000, 48)]
+# the batch-1 cases with a long contraction are shapes where the linear layer's planner would split K: the BMM has
+# no workspace to split into and must finish them in one kernel
+BMM_CASES = [(1, 16, 16, 16), (3, 100, 72, 128), (5, 300, 260, 128), (2, 512, 512, 64), (7, 33, 1000, 48),
+             (1, 64, 512, 2048), (1, 512, 512, 4096), (1, 16, 256, 1024), (1, 100, 4608, 1024)]
 
 
 @pytest.mark.parametrize("b,m,n,k", BMM_CASES)
@@ -192,7 +194,7 @@ def test_bmm_qk_parity(b, m, n, k, odt):
     ref = oracle.w8a8_bmm(a, bt, True, alpha, odt)
     c = sq.w8a8_bmm(dev(a), dev(bt), True, alpha, torch_dtype(odt))
     d = ulp_distance(bits_from_dev(c), ref)
-    assert d.max() <= 1 and (d == 0).mean() > 0.999
+    assert_identical_16(d)
 
 
 BMM_PV_CASES = [(1, 16, 16, 16), (3, 100, 128, 256), (2, 300, 64, 528), (2, 512, 128, 1024), (2, 64, 272, 128),
@@ -210,7 +212,7 @@ def test_bmm_pv_parity(b, m, n, k, odt):
     ref = oracle.w8a8_bmm(a, bn, False, alpha, odt)
     c = sq.w8a8_bmm(dev(a), dev(bn), False, alpha, torch_dtype(odt))
     d = ulp_distance(bits_from_dev(c), ref)
-    assert d.max() <= 1 and (d == 0).mean() > 0.999
+    assert_identical_16(d)
 
 
 def test_attention_chain_small():
@@ -281,8 +283,24 @@ def test_ln_quantize(t, c_i, dtype):
     q, s = sq.ln_quantize(to_dev_16(x, dtype), dev(gamma_f), dev(beta_f))
     q = q.cpu().numpy().astype(np.int32)
     assert np.abs(q - q_ref.astype(np.int32)).max() <= 1
-    assert (q != q_ref).mean() <= 2e-3
+    assert (q != q_ref).mean() <= 1e-3
     assert np.allclose(s.cpu().numpy(), s_ref, rtol=1e-5)
+
+
+def test_softmax_masked_scores():
+    """Scores of -inf (masked positions) take probability 0; a fully masked row gets codes 0, not NaN codes.
+    The finite part of each row is checked against the oracle on the unmasked columns alone (a -inf score adds
+    exactly 0 to the sum, so the remaining probabilities are those of the shorter row)."""
+    _progress("softmax with masked scores")
+    rows, cols, keep = 6, 256, 96
+    sc = (synth.normal_fp16((rows, cols), 72).astype(np.float32) * 2).astype(np.float16)
+    sc[:, keep:] = -np.inf
+    sc[3, :] = -np.inf
+    pq = sq.softmax_quant_p(to_dev_16(sc, F16)).cpu().numpy().astype(np.int32)
+    assert not pq[:, keep:].any() and not pq[3].any()
+    ref = oracle.softmax_quant_p(np.ascontiguousarray(sc[:, :keep]), F16).astype(np.int32)
+    live = [0, 1, 2, 4, 5]
+    assert np.abs(pq[live, :keep] - ref[live]).max() <= 1 and (pq[live, :keep] != ref[live]).mean() <= 1e-3
 
 
 # ------------------------------------------------------------------ argument errors (host side, before any launch)

@@ -7,7 +7,7 @@ import torch
 import oracle
 from paper_2211_10438_amd import binding as sq
 from paper_2211_10438_amd import synth
-from tests._util import (BF16, F16, bits_from_dev, dev, random_bf16_bits, rows_to_tiled_dev, tiled_to_rows, to_dev_16,
+from tests._util import (assert_identical_16, BF16, F16, bits_from_dev, dev, random_bf16_bits, rows_to_tiled_dev, tiled_to_rows, to_dev_16,
                          torch_dtype, ulp_distance)
 
 pytestmark = pytest.mark.gpu
@@ -81,7 +81,7 @@ def test_linear_tiled_end_to_end(t, c_i, c_o, odt, use_bias, relu, use_res):
     y = sq.w8a8_linear(xq, xs, wq, ws, torch_dtype(odt), bias=None if bias is None else dev(bias),
                        residual=None if res is None else to_dev_16(res, odt), relu=relu, layout=sq.TILED)
     d = ulp_distance(bits_from_dev(y), ref)
-    assert d.max() <= 1 and (d == 0).mean() > 0.999
+    assert_identical_16(d)
 
 
 def test_ln_quantize_tiled_matches_row_major():

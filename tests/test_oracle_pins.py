@@ -362,6 +362,51 @@ def test_softmax_quant_special_cases():
     assert np.array_equal(oracle.softmax_quant_p(si + np.float16(4.0), F16), oracle.softmax_quant_p(si, F16))
 
 
+def _bf16_bits(f32: np.ndarray) -> np.ndarray:
+    """fp32 -> bf16 bit patterns, nearest-even (input plumbing for the pins; values used here are exact in bf16
+    or compared through torch's own conversion)."""
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(f32, np.float32)).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+
+
+def test_softmax_quant_special_cases_bf16():
+    """The bf16 branch of the softmax + P quantization (Sec. 4: softmax stays in the 16-bit type, P gets the fixed
+    step 1/127): probabilities are rounded to bf16 (8 significant bits) before the multiplication by 127."""
+    import torch
+    from scipy.special import softmax
+    z = _bf16_bits(np.zeros((1, 8), np.float32))  # uniform row: p = 1/8 exactly (a power of two) -> round(15.875) = 16
+    assert oracle.softmax_quant_p(z, BF16).tolist() == [[16] * 8]
+    # uniform row of 3: p = 1/3 -> bf16(1/3) = 0.333984375 (0x3EAB) -> 42.416 -> 42; in fp16 1/3 -> 0.33325 -> 42.32 -> 42
+    z = _bf16_bits(np.full((1, 3), 1.5, np.float32))
+    assert oracle.softmax_quant_p(z, BF16).tolist() == [[42] * 3]
+    # uniform row of 5: p = 0.2 -> bf16 0.2001953125 (0x3E4D) -> 25.4248 -> 25
+    assert oracle.softmax_quant_p(_bf16_bits(np.zeros((1, 5), np.float32)), BF16).tolist() == [[25] * 5]
+    # a case where bf16 rounding of p changes the code: two scores 0 and ln(3)-ish. Take scores (0, 1): p = (0.26894, 0.73106);
+    # bf16: 0.26953125 (0x3E8A) -> 34.23 -> 34; 0.73046875 (0x3F3B) -> 92.77 -> 93; (fp16 gives 34.16 -> 34 and 92.84 -> 93)
+    assert oracle.softmax_quant_p(_bf16_bits(np.array([[0.0, 1.0]], np.float32)), BF16).tolist() == [[34, 93]]
+    d = np.full((1, 6), -20.0, np.float32)
+    d[0, 2] = 20.0  # one dominant score
+    assert oracle.softmax_quant_p(_bf16_bits(d), BF16).tolist() == [[0, 0, 127, 0, 0, 0]]
+    # random rows against the textbook softmax (scipy, fp64) rounded to bf16 by torch, then round(127 p)
+    rng = np.random.default_rng(43)
+    sb = _bf16_bits((rng.standard_normal((32, 300)) * 3).astype(np.float32))
+    s64 = oracle.f32_from_bits16(sb, BF16).astype(np.float64)
+    p_bf = torch.from_numpy(softmax(s64, axis=-1)).to(torch.bfloat16).to(torch.float32).numpy()
+    want = np.rint(p_bf * np.float32(127.0)).astype(np.int8)
+    got = oracle.softmax_quant_p(sb, BF16)
+    assert np.array_equal(got, want)
+    # the two 16-bit types must really differ somewhere (a branch that ignored the dtype would pass the rows above
+    # only by accident): same real scores, fp16 vs bf16 rounding of p
+    s16 = s64.astype(np.float16)
+    same_scores = np.array_equal(s16.astype(np.float64), s64)
+    if same_scores:
+        assert not np.array_equal(oracle.softmax_quant_p(s16, F16), got)
+    # shift invariance with an exactly representable shift
+    si = _bf16_bits(np.rint(s64).astype(np.float32))
+    sj = _bf16_bits(np.rint(s64).astype(np.float32) + np.float32(4.0))
+    assert np.array_equal(oracle.softmax_quant_p(si, BF16), oracle.softmax_quant_p(sj, BF16))
+
+
 def test_ln_quantize_properties():
     rng = np.random.default_rng(51)
     t, c_i = 6, 512
