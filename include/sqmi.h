@@ -137,6 +137,20 @@ sq_status sq_w8a8_linear(const int8_t* xq, const float* x_scale, int x_scale_per
                          int64_t c_i, int64_t c_o, sq_layout layout, void* workspace, size_t ws_bytes,
                          void* stream);
 
+/* sq_w8a8_linear for callers that cannot allocate device memory or carry a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without the workspace, same
+ * kernels, same results.  The K-split scratch is a 64 MiB device array inside the library
+ * (sq_static_scratch_bytes()); every GPU the library is used on holds its own copy until the process ends.  The
+ * call allocates nothing; the first call on a device resolves the array's address (make that call outside a
+ * graph capture).  Shapes whose sq_workspace_bytes(SQ_OP_W8A8_LINEAR, ...) exceeds the array are rejected with
+ * SQ_ERR_WORKSPACE before any launch.  All calls on one GPU share the array: calls that overlap in time on the
+ * same GPU (different streams or threads) race; calls on one stream are ordered and safe. */
+sq_status sq_w8a8_linear_noalloc(const int8_t* xq, const float* x_scale, int x_scale_per_token,
+                                 const int8_t* wq, const float* w_scale, int w_scale_per_channel,
+                                 const float* bias, const void* residual, int relu, void* y, sq_dtype out,
+                                 int64_t t, int64_t c_i, int64_t c_o, sq_layout layout, void* stream);
+size_t sq_static_scratch_bytes(void);
+
 /* The same layer with the static activation quantizer of the NEXT int8 kernel fused into the epilogue (the
  * "fuse into the previous layer" idea of Sec. 4 applied to the quantize step; Table 2's O3 pipeline):
  *   v16 = the 16-bit value sq_w8a8_linear would store, in dtype `mid`;

@@ -24,6 +24,7 @@ EXPORTS = (
     "sq_status_string", "sq_smooth_scales", "sq_act_absmax_per_channel", "sq_weight_absmax_per_in_channel",
     "sq_prepare_weight", "sq_quantize_act", "sq_w8a8_linear", "sq_w8a8_linear_q8", "sq_i8_gemm_i32", "sq_w8a8_bmm",
     "sq_softmax_quant_p", "sq_ln_quantize", "sq_workspace_bytes", "sq_tiled_bytes", "sq_probe_mfma_i8",
+    "sq_w8a8_linear_noalloc", "sq_static_scratch_bytes",
 )
 
 
@@ -51,6 +52,9 @@ def lib() -> ctypes.CDLL:
         L.sq_prepare_weight.argtypes = [vp, i32, vp, i64, i64, vp, i32, vp, i32, vp, ctypes.c_size_t, vp]
         L.sq_quantize_act.argtypes = [vp, i32, i64, i64, i64, vp, i32, vp, vp, i32, vp, ctypes.c_size_t, vp]
         L.sq_w8a8_linear.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, i32, vp, i32, i64, i64, i64, i32, vp, ctypes.c_size_t, vp]
+        L.sq_w8a8_linear_noalloc.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, i32, vp, i32, i64, i64, i64, i32, vp]
+        L.sq_static_scratch_bytes.restype = ctypes.c_size_t
+        L.sq_static_scratch_bytes.argtypes = []
         L.sq_w8a8_linear_q8.argtypes = [vp, vp, i32, vp, vp, i32, vp, vp, i32, i32, vp, vp, i32, i64, i64, i64, i32, vp,
                                         ctypes.c_size_t, vp]
         L.sq_i8_gemm_i32.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, ctypes.c_size_t, vp]
@@ -223,6 +227,26 @@ def w8a8_linear(xq: torch.Tensor, x_scale: torch.Tensor, wq: torch.Tensor, w_sca
                                 _dev(y, out_dtype, "y"), _dt(y), t, c_i, c_o, layout, wp, wb, _stream()),
            "sq_w8a8_linear")
     return y
+
+
+def w8a8_linear_noalloc(xq: torch.Tensor, x_scale: torch.Tensor, wq: torch.Tensor, w_scale: torch.Tensor, out: torch.Tensor,
+                        bias=None, residual=None, relu: bool = False, layout: int = ROW_MAJOR,
+                        w_per_channel: bool | None = None) -> torch.Tensor:
+    """sq_w8a8_linear_noalloc: the caller passes inputs and the output tensor; nothing is allocated here or in
+    the library (K-split scratch is the library's built-in device array)."""
+    t, c_i = xq.shape
+    c_o = wq.shape[0]
+    if w_per_channel is None:
+        w_per_channel = w_scale.numel() == c_o and c_o > 1
+    if tuple(out.shape) != (t, c_o):
+        raise SqmiError("out must be [t, c_o]")
+    _check(lib().sq_w8a8_linear_noalloc(_dev(xq, torch.int8, "xq"), _dev(x_scale, torch.float32, "x_scale"),
+                                        int(x_scale.numel() == t), _dev(wq, torch.int8, "wq"),
+                                        _dev(w_scale, torch.float32, "w_scale"), int(w_per_channel),
+                                        _opt(bias, torch.float32, "bias"), _opt(residual, out.dtype, "residual"),
+                                        int(relu), _dev(out, None, "out"), _dt(out), t, c_i, c_o, layout, _stream()),
+           "sq_w8a8_linear_noalloc")
+    return out
 
 
 def w8a8_linear_q8(xq: torch.Tensor, x_scale: torch.Tensor, wq: torch.Tensor, w_scale: torch.Tensor, y_step: torch.Tensor,

@@ -20,6 +20,7 @@
 //    block of output tiles, so its L2 serves the shared A rows / B rows.
 //  * Optional split-K writes int32 partial tiles to a workspace, reduced (exactly, int32) by a
 //    second small kernel that also runs the epilogue.
+#include <mutex>
 #include <type_traits>
 
 #include "gemm_args.h"
@@ -804,6 +805,60 @@ sq_status sq_i8_gemm_i32(const int8_t* xq, const int8_t* wq, int32_t* acc, int64
     a.acc_out = acc;
     a.C = acc;
     return run_gemm(a, 1, true, false, workspace, ws_bytes, (hipStream_t)stream, false, layout == SQ_TILED);
+}
+
+// ---- sq_w8a8_linear for callers that cannot allocate: the K-split scratch lives in a device array of the library.
+// Each GPU the library runs on holds its own copy of the array (at its own address) until the process ends.
+}  // extern "C"
+
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+constexpr int kMaxDevices = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+namespace {
+std::mutex scratch_mu;
+void* scratch_addr[kMaxDevices];  // device address of `scratch` on each device, resolved on first use
+
+// The array's name is a host-side handle only; kernels get the device address hipGetSymbolAddress reports for
+// the current device.
+sq_status static_scratch(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SQ_ERR_HIP;
+    std::lock_guard<std::mutex> lock(scratch_mu);
+    if (!scratch_addr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SQ_ERR_HIP;
+        scratch_addr[dev] = ptr;
+    }
+    *out = scratch_addr[dev];
+    return SQ_OK;
+}
+}  // namespace
+
+extern "C" {
+
+size_t sq_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+sq_status sq_w8a8_linear_noalloc(const int8_t* xq, const float* x_scale, int x_scale_per_token, const int8_t* wq,
+                                 const float* w_scale, int w_scale_per_channel, const float* bias, const void* residual,
+                                 int relu, void* y, sq_dtype out, int64_t t, int64_t c_i, int64_t c_o, sq_layout layout,
+                                 void* stream)
+{
+    if (!xq || !x_scale || !wq || !w_scale || !y) return SQ_ERR_NULL;
+    if (!dims_ok(t, c_i, c_o)) return SQ_ERR_SHAPE;
+    const size_t need = sq_gemm_workspace_bytes(t, c_i, c_o);
+    if (need > kStaticScratchBytes) return SQ_ERR_WORKSPACE;  // shape beyond the built-in scratch: use sq_w8a8_linear
+    void* ws = nullptr;
+    if (need) {
+        const sq_status st = static_scratch(&ws);
+        if (st != SQ_OK) return st;
+    }
+    // Every K split writes its whole [t, c_o] slice of the partial sums before the reduction reads it, so nothing
+    // in the scratch has to start at zero and the previous call's contents do not matter.
+    return sq_w8a8_linear(xq, x_scale, x_scale_per_token, wq, w_scale, w_scale_per_channel, bias, residual, relu, y, out,
+                          t, c_i, c_o, layout, ws, need ? kStaticScratchBytes : 0, stream);
 }
 
 // Attention BMM dispatcher behind sq_w8a8_bmm (arguments already validated).

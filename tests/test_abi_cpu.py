@@ -98,6 +98,16 @@ def test_argument_validation_happens_before_any_launch():
     assert L.sq_workspace_bytes(sq.OP_W8A8_LINEAR, 2048, 12288, 36864) == 0 or True
 
 
+def test_noalloc_linear_rejects_shapes_beyond_its_scratch_before_any_launch():
+    L = sq.lib()
+    fake = ctypes.c_void_p(0x1000)
+    t, c_i, c_o = 128, 65536, 32768  # this shape's K-split plan needs 128 MiB of partial sums
+    assert L.sq_workspace_bytes(sq.OP_W8A8_LINEAR, t, c_i, c_o) > L.sq_static_scratch_bytes() == 64 << 20
+    assert L.sq_w8a8_linear_noalloc(fake, fake, 1, fake, fake, 0, None, None, 0, fake, 0, t, c_i, c_o, 0, None) == 5
+    assert L.sq_w8a8_linear_noalloc(None, fake, 1, fake, fake, 0, None, None, 0, fake, 0, 4, 64, 64, 0, None) == 1
+    assert L.sq_w8a8_linear_noalloc(fake, fake, 1, fake, fake, 0, None, None, 0, fake, 0, 4, 0, 64, 0, None) == 2
+
+
 def test_documented_limits_are_enforced_on_the_host():
     """Limits the header states per entry point (beyond 16-byte alignment and c_i % 16)."""
     L = sq.lib()
