@@ -116,7 +116,12 @@ sq_status sq_prepare_weight(const void* w, sq_dtype dtype, const float* s, int64
  * scale: device fp32; written in the dynamic modes ([t] per token, [1] per tensor), read in
  *   SQ_PER_TENSOR_STATIC ([1], the calibrated Delta);
  * xq: device int8 [t, c_i] in layout `xq_layout`;  workspace: device, needed for
- *   SQ_PER_TENSOR_DYNAMIC only. */
+ *   SQ_PER_TENSOR_DYNAMIC only: with sq_workspace_bytes(SQ_OP_QUANTIZE_ACT, ...) bytes, tensors of up to
+ *   512 x 16384 elements run as one launch and cross HBM once (the maximum and the rounding are separated inside
+ *   the kernel by a bounded wait on an arrival count; should the wait ever expire, scale[0] = NaN and no code is
+ *   written).  Larger tensors, a smaller workspace (at least 4 bytes) or a stream under graph capture run as
+ *   three launches with identical results.  The workspace needs no initialisation; concurrent calls must not
+ *   share it. */
 sq_status sq_quantize_act(const void* x, sq_dtype dtype, int64_t t, int64_t c_i, int64_t ldx,
                           const float* inv_s, sq_act_mode mode, float* scale, int8_t* xq,
                           sq_layout xq_layout, void* workspace, size_t ws_bytes, void* stream);

@@ -195,8 +195,11 @@ def quantize_act(x: torch.Tensor, mode: int, inv_s: torch.Tensor | None = None, 
             scale = torch.empty(t if mode == PER_TOKEN_DYNAMIC else 1, dtype=torch.float32, device=x.device)
     else:
         xq, scale = out
-    wp, wb, keep = _workspace(workspace_bytes(OP_QUANTIZE_ACT, t, c_i, 0) if mode == PER_TENSOR_DYNAMIC else 0,
-                              x.device, workspace)
+    if workspace is not None:  # passed through as it is: a small one selects the library's three-launch O2 path
+        wp, wb, keep = workspace.data_ptr(), workspace.numel() * workspace.element_size(), workspace
+    else:
+        wp, wb, keep = _workspace(workspace_bytes(OP_QUANTIZE_ACT, t, c_i, 0) if mode == PER_TENSOR_DYNAMIC else 0,
+                                  x.device, None)
     _check(lib().sq_quantize_act(x_ptr, _dt(x), t, c_i, ldx, _opt(inv_s, torch.float32, "inv_s"), mode,
                                  _dev(scale, torch.float32, "scale"), _dev(xq, torch.int8, "xq"), layout, wp, wb,
                                  _stream()), "sq_quantize_act")

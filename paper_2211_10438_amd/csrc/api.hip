@@ -4,6 +4,7 @@
 
 #include "common.h"
 
+extern "C" size_t sq_quantize_workspace_bytes(void);
 extern "C" size_t sq_gemm_workspace_bytes(int64_t t, int64_t c_i, int64_t c_o);
 extern "C" sq_status sq_internal_bmm(const int8_t* a, const int8_t* b, int trans_b, float alpha, void* c, sq_dtype out,
                                      int64_t batch, int64_t m, int64_t n, int64_t k, int64_t stride_a, int64_t stride_b,
@@ -51,7 +52,7 @@ size_t sq_tiled_bytes(int64_t rows, int64_t k)
 size_t sq_workspace_bytes(sq_op op, int64_t t, int64_t c_i, int64_t c_o)
 {
     switch (op) {
-        case SQ_OP_QUANTIZE_ACT: return 16;
+        case SQ_OP_QUANTIZE_ACT: return sq_quantize_workspace_bytes();  // partial maxima of the O2 mode
         case SQ_OP_PREPARE_WEIGHT: return 16 + (c_o > 0 ? (size_t)c_o * sizeof(uint32_t) : 0);  // column maxima (per-channel steps)
         case SQ_OP_W8A8_LINEAR:
         case SQ_OP_I8_GEMM_I32: return sq_gemm_workspace_bytes(t, c_i, c_o);

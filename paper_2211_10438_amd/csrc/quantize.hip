@@ -5,8 +5,20 @@
 // handled by a 256-thread workgroup (wide rows) or by one 64-lane wave (narrow rows, reduction
 // with cross-lane shuffles only).
 // Per-tensor static (O3): pure elementwise pass, saturating.
-// Per-tensor dynamic (O2): an absmax pass (atomic max on the bit pattern of a non-negative float)
-// followed by the elementwise pass.
+// Per-tensor dynamic (O2): tensors of up to 512 x 16384 elements run as ONE ordinary launch and cross HBM once.
+// Workgroup b loads its 16384 elements into registers, stores its absmax to partial[b] (plain store: nothing to
+// clear), adds 1 to an arrival count and waits until the count reaches the grid size; then every workgroup reduces
+// the partial maxima and quantizes its registers.  The grid is at most 512 workgroups (a quarter of what the
+// device keeps resident; the occupancy query sizes it), so every workgroup gets a slot while the others wait; the
+// wait is bounded all the same (spin limit; on expiry scale[0] = NaN and nothing is quantized), so every wave
+// leaves the kernel whatever happens.  The arrival count carries a per-call ticket in its upper half, so a stale
+// workspace counts as zero.  Same-address atomics cost about 30 ns each on this part and serialize, which is why
+// larger tensors (more workgroups, and the second read served by the memory-side cache anyway), streams under HIP
+// graph capture (a replay would reuse the ticket) and callers with a small workspace get the three-launch version
+// (clear, absmax with atomic max on the float's bit pattern, quantize); results are identical.
+#include <atomic>
+#include <chrono>
+
 #include "common.h"
 
 namespace {
@@ -240,6 +252,92 @@ __global__ __launch_bounds__(256) void quant_per_tensor_kernel(const uint16_t* _
     }
 }
 
+// ---- ticketed 64-bit cells {ticket : value}.  A cell whose upper half is not this call's ticket is stale: the
+// first workgroup that sees it so replaces it by {ticket : 0} (one compare-and-swap; it fails only if another
+// workgroup of the same call was faster, which is just as good).  After that the cell is updated with the
+// hardware's 64-bit add / max, which never touch the ticket half.
+SQ_DEVICE void ticket_open(unsigned long long* cell, uint32_t ticket)
+{
+    unsigned long long v = __hip_atomic_load(cell, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((uint32_t)(v >> 32) != ticket)
+        __hip_atomic_compare_exchange_strong(cell, &v, (unsigned long long)ticket << 32, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
+}
+
+constexpr int kO2MaxGrid = 512;  // workgroups of the single-launch kernel (= partial maxima in the workspace)
+
+// Workspace layout: bytes [0, 8) arrival cell {ticket : count}; bytes [256, 256 + 4 * kO2MaxGrid) partial maxima.
+// spin_limit bounds the wait (0.5 to 2 us per poll); it is not reached unless a workgroup of the grid never gets to
+// run, and if it is, scale[0] becomes NaN and nothing is quantized: every wave still leaves the kernel.
+template <bool BF16, int NV>
+__global__ __launch_bounds__(256) void quant_per_tensor_single_kernel(const uint16_t* __restrict__ x, int64_t ldx, int c_i, int64_t t,
+                                                                     const float* __restrict__ inv_s, float* scale,
+                                                                     unsigned char* ws, uint32_t ticket, uint32_t spin_limit,
+                                                                     int8_t* __restrict__ xq, bool tiled)
+{
+    __shared__ float red[4];
+    __shared__ uint32_t ok_flag;
+    unsigned long long* cell = (unsigned long long*)ws;
+    uint32_t* partial = (uint32_t*)(ws + 256);
+    const int nvec = c_i >> 3;
+    const int64_t total = t * (int64_t)nvec;
+    const int64_t g0 = (int64_t)blockIdx.x * (256 * NV) + threadIdx.x;
+    v4u raw[NV];
+    float m = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int64_t g = g0 + i * 256;
+        raw[i] = v4u{0, 0, 0, 0};
+        if (g < total) {
+            const int64_t row = g / nvec;
+            const int idx = (int)(g - row * nvec);
+            raw[i] = __builtin_nontemporal_load((const v4u*)(x + row * ldx) + idx);
+            float f[8];
+            unpack8<BF16>(raw[i], f);
+            if (inv_s) smooth8(f, inv_s, idx * 8);
+            m = __builtin_fmaxf(m, absmax8(f));
+        }
+    }
+    m = block_max_256(m, red);
+    if (threadIdx.x == 0) {
+        __hip_atomic_store(partial + blockIdx.x, __builtin_bit_cast(uint32_t, m), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ticket_open(cell, ticket);
+        // release: the partial maximum above is visible device-wide before the count moves
+        __hip_atomic_fetch_add(cell, 1ull, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        uint32_t spins = 0;
+        bool ok = true;
+        while ((uint32_t)__hip_atomic_load(cell, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < gridDim.x) {
+            if (++spins > spin_limit) { ok = false; break; }
+            if (spins < 16) __builtin_amdgcn_s_sleep(16); else __builtin_amdgcn_s_sleep(64);
+        }
+        ok_flag = ok ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!ok_flag) {  // the wait gave up (see above)
+        if (threadIdx.x == 0) scale[0] = __builtin_nanf("");
+        return;
+    }
+    float a = 0.0f;
+    for (int i = threadIdx.x; i < (int)gridDim.x; i += 256)
+        a = __builtin_fmaxf(a, __builtin_bit_cast(float, __hip_atomic_load(partial + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)));
+    __syncthreads();  // `red` is reused
+    a = block_max_256(a, red);
+    const float r = a > 0.0f ? 127.0f / a : 0.0f;
+    if (blockIdx.x == 0 && threadIdx.x == 0) scale[0] = a / 127.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int64_t g = g0 + i * 256;
+        if (g < total) {
+            const int64_t row = g / nvec;
+            const int idx = (int)(g - row * nvec);
+            float f[8];
+            unpack8<BF16>(raw[i], f);
+            if (inv_s) smooth8(f, inv_s, idx * 8);
+            __builtin_nontemporal_store(quant8(f, r), (v2u*)code_dst(xq, row, idx * 8, c_i, tiled));
+        }
+    }
+}
+
 // Per-channel calibration statistic: out_j = max_t |x_tj| (bit patterns, see above).
 template <bool BF16>
 __global__ __launch_bounds__(256) void act_absmax_per_channel_kernel(const uint16_t* __restrict__ x, int c_i, int64_t t,
@@ -291,9 +389,39 @@ int grid_for(int64_t work_items)
     return (int)(blocks < 1 ? 1 : (blocks > cap ? cap : blocks));
 }
 
+constexpr int kO2NV = 8;  // 16-byte vectors a thread holds: a workgroup covers 256 x 8 x 8 = 16384 elements
+
+// Ticket of one single-launch O2 call: a per-process counter started from the clock, never 0.
+uint32_t next_ticket()
+{
+    static std::atomic<uint32_t> counter{(uint32_t)std::chrono::steady_clock::now().time_since_epoch().count() * 2654435761u};
+    uint32_t v = counter.fetch_add(1u, std::memory_order_relaxed) + 1u;
+    return v ? v : counter.fetch_add(1u, std::memory_order_relaxed) + 1u;
+}
+
+// Largest grid of the single-launch kernel: a quarter of the workgroups the device keeps resident (occupancy x
+// compute units), at most kO2MaxGrid.
+template <bool BF16> int single_launch_grid()
+{
+    static int limit = -1;
+    if (limit < 0) {
+        int dev = 0, cus = 0, per_cu = 0;
+        limit = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0 &&
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, quant_per_tensor_single_kernel<BF16, kO2NV>, 256, 0) == hipSuccess &&
+            per_cu > 0)
+            limit = cus * per_cu / 4 < kO2MaxGrid ? cus * per_cu / 4 : kO2MaxGrid;
+    }
+    return limit;
+}
+
 }  // namespace
 
 extern "C" {
+
+// Workspace of the per-tensor dynamic mode: arrival cell + partial maxima of the single-launch kernel.
+size_t sq_quantize_workspace_bytes(void) { return 256 + kO2MaxGrid * sizeof(uint32_t); }
 
 sq_status sq_quantize_act(const void* x, sq_dtype dtype, int64_t t, int64_t c_i, int64_t ldx, const float* inv_s,
                           sq_act_mode mode, float* scale, int8_t* xq, sq_layout xq_layout, void* workspace,
@@ -321,6 +449,20 @@ sq_status sq_quantize_act(const void* x, sq_dtype dtype, int64_t t, int64_t c_i,
     const int grid = grid_for(t * (c_i >> 3));
     if (mode == SQ_PER_TENSOR_DYNAMIC) {
         uint32_t* amax = (uint32_t*)workspace;
+        const int64_t vecs = t * (c_i >> 3);
+        const int64_t nwg = (vecs + 256 * kO2NV - 1) / (256 * kO2NV);  // workgroups that hold the whole tensor in registers
+        const int limit = bf ? single_launch_grid<true>() : single_launch_grid<false>();
+        // A stream that is being captured into a HIP graph records the three-launch version: a replay would reuse
+        // the ticket.
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusActive;
+        if (hipStreamIsCapturing(st, &cap) != hipSuccess) cap = hipStreamCaptureStatusActive;
+        if (cap == hipStreamCaptureStatusNone && nwg <= limit && ws_bytes >= sq_quantize_workspace_bytes() &&
+            (reinterpret_cast<uintptr_t>(workspace) & 15u) == 0) {
+            const uint32_t ticket = next_ticket(), spin_limit = 1u << 21;
+            if (bf) sq_launch((quant_per_tensor_single_kernel<true, kO2NV>), dim3((unsigned)nwg), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, (unsigned char*)workspace, ticket, spin_limit, xq, tiled);
+            else sq_launch((quant_per_tensor_single_kernel<false, kO2NV>), dim3((unsigned)nwg), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, (unsigned char*)workspace, ticket, spin_limit, xq, tiled);
+            return sq_launch_status();
+        }
         sq_launch(fill_u32_kernel, dim3(1), dim3(64), 0, st, amax, 0u, 1);
         if (bf) {
             sq_launch(tensor_absmax_kernel<true>, dim3(grid), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, amax);

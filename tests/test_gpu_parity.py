@@ -60,6 +60,26 @@ def test_quantize_per_tensor(mode, t, c_i, dtype):
         assert np.abs(q_ref).max() == 127 and (np.abs(q_ref) == 127).sum() > 1
 
 
+@pytest.mark.parametrize("t,c_i,ldx", [(7, 64, 64), (1000, 4096, 4096), (2500, 9216, 9216), (3000, 4096, 12288)])
+def test_quantize_per_tensor_dynamic_single_launch(t, c_i, ldx):
+    """Table 2's O2 (one dynamic step for the whole tensor) in one launch: tensors that fit the registers of the
+    running workgroups (first two cases), tensors beyond that (23 M elements: the remainder is read twice) and a
+    column slice of a wider matrix.  Checked against the oracle, and against the library's three-launch version,
+    which a caller selects by passing a workspace too small for the kernel's three cells."""
+    _progress(f"O2 single launch t={t} c_i={c_i} ldx={ldx}")
+    full = synth.normal_fp16((t, ldx), 2100 + t)
+    full[t // 2, c_i // 3] = np.float16(9.5)  # a unique maximum somewhere in the middle
+    x = np.ascontiguousarray(full[:, :c_i])
+    q_ref, s_ref = oracle.quantize_act(x, F16, oracle.PER_TENSOR_DYNAMIC)
+    xd = to_dev_16(full, F16)[:, :c_i]
+    q1, s1 = sq.quantize_act(xd, sq.PER_TENSOR_DYNAMIC)
+    small_ws = torch.empty(16, dtype=torch.uint8, device="cuda")
+    q3, s3 = sq.quantize_act(xd, sq.PER_TENSOR_DYNAMIC, workspace=small_ws)
+    assert s1.item() == s_ref[0] == s3.item()
+    assert torch.equal(q1, q3)
+    assert np.array_equal(q1.cpu().numpy(), q_ref)
+
+
 def test_quantize_degenerate_rows_and_stride():
     _progress("quantize zero rows / row stride")
     x = synth.normal_fp16((6, 96), 3)
