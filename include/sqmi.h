@@ -184,6 +184,26 @@ sq_status sq_w8a8_bmm(const int8_t* a, const int8_t* bm, int trans_b, float alph
                       sq_dtype out, int64_t b, int64_t m, int64_t n, int64_t k, int64_t stride_a,
                       int64_t stride_b, int64_t stride_c, void* stream);
 
+/* The INT8 attention block of Sec. 4 in one kernel -- both batched matmuls in INT8, the softmax in the 16-bit
+ * floating type -- without the [s_q, s_k] score and probability tensors ever reaching memory:
+ *   s_ij = round_to_16bit( fl32( float(sum_c q[i, c] k[j, c]) * alpha1 ) )            (sq_w8a8_bmm, trans_b = 1)
+ *   p_ij = round_to_16bit( e^(s_ij - max_j s_ij) / sum_j e^(s_ij - max_j s_ij) ),  pq_ij = round(127 p_ij)   (sq_softmax_quant_p)
+ *   o_ic = round_to_16bit( fl32( float(sum_j pq_ij v[j, c]) * alpha2 ) )              (sq_w8a8_bmm, trans_b = 0)
+ * i.e. the quantization points of the chain of those three calls with `out` as the dtype of s, p and o.  The
+ * integer sums are exact; the exponential and the division are fp32 on the device (as in sq_softmax_quant_p), so
+ * a code pq may differ by one from an fp64 evaluation, rarely.
+ * q: device int8 [b, s_q, d]; k, v: device int8 [b, s_k, d] (row-major, d contiguous); alpha1 (> 0, e.g.
+ * Delta_Q Delta_K / sqrt(d)) and alpha2 (e.g. Delta_V / 127): HOST scalars; o: device [b, s_q, d] of dtype `out`.
+ * Batch strides in elements (multiples of 16 for q, k, v, of 8 for o).
+ * p_codes: NULL, or device int8 [b, s_q, s_k] (4-byte aligned) that receives the codes pq the kernel formed
+ * (inspection and tests; costs their write).
+ * Limits: d = 64 or 128 and s_k % 128 == 0 (else SQ_ERR_UNSUPPORTED: use the three calls above); any s_q.
+ * Needs no workspace. */
+sq_status sq_w8a8_attention(const int8_t* q, const int8_t* k, const int8_t* v, float alpha1, float alpha2,
+                            void* o, sq_dtype out, int64_t b, int64_t s_q, int64_t s_k, int64_t d,
+                            int64_t stride_q, int64_t stride_k, int64_t stride_v, int64_t stride_o,
+                            int8_t* p_codes, void* stream);
+
 /* Row softmax kept in 16-bit floating point (Sec. 4 keeps Softmax in FP16) followed by quantization
  * of the probabilities with the fixed step 1/127: pq = round(p * 127) in [0, 127].
  * s: device [rows, cols] 16-bit scores, packed; pq: device int8 [rows, cols].

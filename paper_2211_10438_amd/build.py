@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libsqmi.so")
-SOURCES = ["api.hip", "quantize.hip", "weight_prep.hip", "rowops.hip", "gemm_i8.hip", "gemm_i8_stream.hip", "bmm_strip.hip", "probe.hip"]
+SOURCES = ["api.hip", "quantize.hip", "weight_prep.hip", "rowops.hip", "gemm_i8.hip", "gemm_i8_stream.hip", "bmm_strip.hip", "attn_fused.hip", "probe.hip"]
 
 # -ffp-contract=off: scale arithmetic must round every product and sum separately (bit-exact codes).
 # packed-fp32 ops are disabled for the whole library.

@@ -1,0 +1,290 @@
+// Fused INT8 attention for gfx950: O = (P_q V_q) * alpha2 with P_q = round(127 * softmax16(S)), S = round16((Q_q K_q^T) * alpha1),
+// in one kernel that never writes the score or probability tensors.
+//
+// The attention block of Sec. 4 runs both batched matmuls in INT8 and keeps the softmax in the 16-bit
+// floating type; the unfused chain (sq_w8a8_bmm, sq_softmax_quant_p, sq_w8a8_bmm) moves the [s_q, s_k]
+// tensors S (16-bit) and P_q (int8) through HBM twice each, 19 of the 20 GB it touches at 768 heads x 2048^2.
+// This kernel keeps the same quantization points -- scores rounded to 16 bits before the softmax,
+// probabilities rounded to 16 bits and then to codes with the fixed step 1/127 -- and recomputes Q K^T
+// instead of storing it:
+//   pass 1  over the key tiles: S tile by MFMA, running row maximum and sum of exponentials (online softmax);
+//   pass 2  over the key tiles again: S tile by MFMA, p = e^(s - m) / l, p16, code = round(127 p16); the 16
+//           codes a lane produces from one 32x32 accumulator block ARE its operand fragment of the P V
+//           MFMA (second operand: row l & 31, contraction bytes 16 (l >> 5) ..), so P_q never leaves registers.
+// One workgroup owns 128 query rows of one (batch, head): four waves of 32 rows, the Q operand fragments in
+// registers for the whole kernel.  K and V tiles of 128 keys travel L2 -> LDS with global_load_lds, double
+// buffered, one s_barrier per tile.  Because the Q K^T MFMA takes the K rows as first operand, an accumulator
+// block is the transpose of its output block: a lane holds, for its row, the columns 8g + 4h + e of a 32-key
+// block (h = l >> 5).  That fixes the order of the contraction bytes of the P V MFMA; the V operand is fetched
+// in the same order with the LDS transpose read (ds_read_b64_tr_b8), whose eight source rows are named by the
+// lanes and can therefore be any eight keys.
+// The kernel is bound by the vector ALU (about 22 issue slots per score over both passes against 0.75 MFMA
+// cycles); two workgroups per compute unit let one wave's MFMAs run under the other's exponentials.
+#include "gemm_args.h"
+
+namespace {
+
+struct AttnArgs {
+    const int8_t* Q;  // [b][s_q, d]
+    const int8_t* K;  // [b][s_k, d]
+    const int8_t* V;  // [b][s_k, d]
+    void* O;          // [b][s_q, d] 16-bit
+    int8_t* P;        // optional [b][s_q, s_k]: the probability codes, for inspection; or NULL
+    int s_q, s_k, tiles_m;
+    int64_t stride_q, stride_k, stride_v, stride_o;  // batch strides in elements
+    float alpha1, alpha2;
+};
+
+constexpr float kLog2e = 1.44269504088896340736f;
+
+template <bool BF16, int HD>
+__global__ __launch_bounds__(256, 2) void attn_i8_kernel(const AttnArgs p)
+{
+    constexpr int TK = 128;               // keys per tile
+    constexpr int SLOT = 16384;           // LDS bytes reserved per tile
+    constexpr int TILE = TK * HD;         // bytes of a K or V tile
+    constexpr int LPT = TILE / 1024 / 4;  // global->LDS loads per wave and tile
+    constexpr int CH = HD / 16;           // 16-byte chunks per row
+    constexpr int RPB = 1024 / HD;        // rows per 1 KB block
+    constexpr int NKS = HD / 32;          // MFMA steps of Q K^T
+    constexpr int NB = HD / 32;           // 32-column blocks of O
+    static_assert(HD == 128 || HD == 64, "head dimension");
+    __shared__ __attribute__((aligned(1024))) char smem[4 * SLOT];  // stage s: K tile at slot 2s, V tile at slot 2s + 1
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r32 = lane & 31, h = lane >> 5;
+
+    // Consecutive workgroup ids go round-robin to the 8 XCDs; give each XCD a contiguous range of the logical
+    // order so that the row blocks of one head (they share its K and V) run on one L2.
+    const int64_t total = gridDim.x;
+    int64_t pid;
+    {
+        const int64_t wg = blockIdx.x, j = wg >> 3;
+        const int xcd = (int)(wg & 7);
+        const int64_t per = total >> 3;
+        const int r = (int)(total & 7);
+        pid = xcd * per + (xcd < r ? xcd : r) + j;
+    }
+    const int batch = (int)(pid / p.tiles_m);
+    const int m0 = (int)(pid - (int64_t)batch * p.tiles_m) * 128;
+    const int nt = p.s_k / TK;
+
+    // ---- LDS images.  K tile: row n at n * HD, its 16-byte chunks XOR-permuted (position = chunk ^ swzK(n)) so
+    // that the operand reads (32 rows, one chunk) spread over the banks.  V tile: row k at k * HD, position =
+    // chunk ^ swzV(k), chosen so that the eight rows of one transpose read sit at eight different positions.
+    auto swzK = [](int r) { return HD == 128 ? (r & 7) : (((r >> 1) & 3) ^ ((r >> 3) & 1)); };
+    auto swzV = [](int k) { return HD == 128 ? ((k & 3) | (((k >> 3) & 1) << 2)) : (k & 3); };
+    uint32_t srcK[LPT], srcV[LPT];
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+        const int row = (i * 4 + wave) * RPB + lane / CH, pos = lane % CH;
+        srcK[i] = (uint32_t)(row * HD + ((pos ^ swzK(row)) * 16));
+        srcV[i] = (uint32_t)(row * HD + ((pos ^ swzV(row)) * 16));
+    }
+    const int8_t* Kb = p.K + (int64_t)batch * p.stride_k;
+    const int8_t* Vb = p.V + (int64_t)batch * p.stride_v;
+    auto issue = [&](int j, int stage, bool with_v) {
+        const int8_t* kt = Kb + (int64_t)j * TILE;
+        char* dk = smem + (2 * stage) * SLOT;
+#pragma unroll
+        for (int i = 0; i < LPT; ++i)
+            __builtin_amdgcn_global_load_lds(GPTR(kt + srcK[i]), LPTR(dk + (i * 4 + wave) * 1024), 16, 0, 0);
+        if (with_v) {
+            const int8_t* vt = Vb + (int64_t)j * TILE;
+#pragma unroll
+            for (int i = 0; i < LPT; ++i)
+                __builtin_amdgcn_global_load_lds(GPTR(vt + srcV[i]), LPTR(dk + SLOT + (i * 4 + wave) * 1024), 16, 0, 0);
+        }
+    };
+
+    // ---- Q operand fragments (second MFMA operand): lane l feeds query row (l & 31) of this wave with the 16
+    // bytes of chunk 2 ks + (l >> 5).  Rows past s_q repeat the last row; they are never stored.
+    v4i fq[NKS];
+    {
+        int row = m0 + wave * 32 + r32;
+        row = row < p.s_q ? row : p.s_q - 1;
+        const int8_t* qp = p.Q + (int64_t)batch * p.stride_q + (int64_t)row * HD;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) fq[ks] = *(const v4i*)(qp + (2 * ks + h) * 16);
+    }
+    // K operand fragment (first operand) of key block jn, step ks: key row 32 jn + (l & 31), chunk 2 ks + (l >> 5)
+    int koff[NKS];
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) koff[ks] = r32 * HD + (((2 * ks + h) ^ swzK(r32)) * 16);
+    // V operand fragment (first operand of the P V MFMA) of key block ks, column block jn: column n = 32 jn + (l & 31),
+    // contraction bytes in the order the codes have in the P fragment: byte 4g + e <-> key 32 ks + 8g + 4h + e.
+    // Within 16 lanes, source lanes 2j and 2j + 1 of a transpose read name the two 8-byte halves of the 16 columns
+    // of one key row, and lane i receives column i of the eight rows: rows j = 0..3 are keys 4h + j, rows 4..7 keys
+    // 8 + 4h + (j - 4); the second read takes the keys 16 further on.
+    int voff;
+    {
+        const int s = lane & 15, j = s >> 1, cb = (lane >> 4) & 1;
+        const int key = 4 * h + (j & 3) + 8 * (j >> 2);
+        voff = key * HD + ((cb ^ swzV(key)) * 16) + (s & 1) * 8;  // chunk 2 jn + cb: jn enters below (XOR on bits 1.., swzV < 8)
+    }
+    auto v_frag = [&](const char* vt, int ks, int jn) {
+        // position of chunk (2 jn + cb) = (2 jn + cb) ^ swz = ((2 jn) ^ (cb ^ swz)) as 2 jn has bit 0 clear
+        const int a = (voff ^ ((2 * jn) << 4)) + ks * 32 * HD;
+        const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) v2i*)(vt + a));
+        const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) v2i*)(vt + a + 16 * HD));
+        return v4i{lo.x, lo.y, hi.x, hi.y};
+    };
+
+    // S tile = Q K^T for the 128 keys of a stage: acc[jn] is the transposed 32x32 block of key block jn
+    auto scores = [&](const char* kt, v16i(&acc)[4]) {
+#pragma unroll
+        for (int jn = 0; jn < 4; ++jn) {
+            const v16i zero = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+            acc[jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(*(const v4i*)(kt + jn * 32 * HD + koff[0]), fq[0], zero, 0, 0, 0);
+        }
+#pragma unroll
+        for (int ks = 1; ks < NKS; ++ks)
+#pragma unroll
+            for (int jn = 0; jn < 4; ++jn)
+                acc[jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(*(const v4i*)(kt + jn * 32 * HD + koff[ks]), fq[ks], acc[jn], 0, 0, 0);
+    };
+    // score of one accumulator as the 16-bit tensor element it stands for, widened again: round16(fl32(acc * alpha1))
+    const float alpha1 = p.alpha1;
+    auto s16f = [&](int a) { return load16_bits<BF16>(store16_bits<BF16>((float)a * alpha1)); };
+
+    // ---- pass 1: row maximum m and l = sum e^(s - m), online.  The maximum is taken on the integer accumulators
+    // (s is monotone in acc: alpha1 > 0).  A row's scores are split between lanes r and r + 32.
+    float m_run = -__builtin_inff(), l_run = 0.0f;
+    issue(0, 0, false);
+    for (int j = 0; j < nt; ++j) {
+        wait_vmcnt_imm<0>();           // this wave's part of tile j has landed
+        __builtin_amdgcn_s_barrier();  // ... everybody's has, and everybody is done with tile j - 1
+        if (j + 1 < nt) issue(j + 1, (j + 1) & 1, false);
+        v16i acc[4];
+        scores(smem + (2 * (j & 1)) * SLOT, acc);
+        int imax = acc[0][0];
+#pragma unroll
+        for (int jn = 0; jn < 4; ++jn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) imax = acc[jn][v] > imax ? acc[jn][v] : imax;
+        const int other = __shfl_xor(imax, 32, 64);
+        imax = other > imax ? other : imax;
+        const float m_new = __builtin_fmaxf(m_run, s16f(imax));
+        l_run *= __builtin_amdgcn_exp2f((m_run - m_new) * kLog2e);
+        m_run = m_new;
+        const float nm = -m_new * kLog2e;
+        float part = 0.0f;
+#pragma unroll
+        for (int jn = 0; jn < 4; ++jn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) part += __builtin_amdgcn_exp2f(__builtin_fmaf(s16f(acc[jn][v]), kLog2e, nm));
+        l_run += part;
+    }
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float inv = 1.0f / l_tot;
+    const float nm = -m_run * kLog2e;
+
+    // ---- pass 2: codes and P V.
+    v16i acc_o[NB];
+#pragma unroll
+    for (int jn = 0; jn < NB; ++jn)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc_o[jn][v] = 0;
+    int8_t* Prow = nullptr;
+    if (p.P) {
+        const int row = m0 + wave * 32 + r32;
+        if (row < p.s_q) Prow = p.P + ((int64_t)batch * p.s_q + row) * (int64_t)p.s_k + 4 * h;
+    }
+    __syncthreads();  // every wave is done with the last tile of pass 1 before its buffer is refilled
+    issue(0, 0, true);
+    for (int j = 0; j < nt; ++j) {
+        wait_vmcnt_imm<0>();
+        __builtin_amdgcn_s_barrier();
+        if (j + 1 < nt) issue(j + 1, (j + 1) & 1, true);
+        const char* kt = smem + (2 * (j & 1)) * SLOT;
+        const char* vt = kt + SLOT;
+        v16i acc[4];
+        scores(kt, acc);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            // the 16 codes of this lane for key block ks: word g holds columns 8g + 4h + 0..3
+            v4i fp;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                uint32_t q[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float ex = __builtin_amdgcn_exp2f(__builtin_fmaf(s16f(acc[ks][4 * g + e]), kLog2e, nm));
+                    const float p16 = load16_bits<BF16>(store16_bits<BF16>(ex * inv));  // the softmax output is a 16-bit tensor
+                    q[e] = __builtin_bit_cast(uint32_t, __builtin_fmaf(p16, 127.0f, 12582912.0f));  // round(127 p16), exact product
+                }
+                fp[g] = (int)pack4_low_bytes(q[0], q[1], q[2], q[3]);
+            }
+            if (Prow) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) *(int*)(Prow + j * TK + ks * 32 + 8 * g) = fp[g];
+            }
+#pragma unroll
+            for (int jn = 0; jn < NB; ++jn)
+                acc_o[jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(v_frag(vt, ks, jn), fp, acc_o[jn], 0, 0, 0);
+        }
+    }
+
+    // ---- epilogue: o = round16(fl32(acc * alpha2)).  Accumulator block jn is the transposed output block: lane l,
+    // register v holds row (l & 31), column 32 jn + 8 (v / 4) + 4 (l >> 5) + (v & 3).  Each wave stages its 32 rows in
+    // its own part of the (now free) tile buffers and writes whole rows in 16-byte pieces.
+    constexpr int PITCH = HD * 2 + 16;
+    __syncthreads();
+    char* stg = smem + wave * SLOT;
+    const float alpha2 = p.alpha2;
+#pragma unroll
+    for (int jn = 0; jn < NB; ++jn)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            uint32_t o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = dequant_one<BF16>(acc_o[jn][4 * g + e], alpha2, 0.0f, false, false, 0u, false);
+            *(v2u*)(stg + r32 * PITCH + (32 * jn + 8 * g + 4 * h) * 2) = v2u{o[0] | (o[1] << 16), o[2] | (o[3] << 16)};
+        }
+    __builtin_amdgcn_wave_barrier();
+    uint16_t* Ob = (uint16_t*)p.O + (int64_t)batch * p.stride_o;
+    constexpr int CPR = HD / 8;  // 16-byte pieces per row
+#pragma unroll
+    for (int it = 0; it < 32 * CPR / 64; ++it) {
+        const int idx = it * 64 + lane, r = idx / CPR, c = idx - r * CPR;
+        const int row = m0 + wave * 32 + r;
+        const v4u val = *(const v4u*)(stg + r * PITCH + c * 16);
+        if (row < p.s_q) __builtin_nontemporal_store(val, (v4u*)(Ob + (int64_t)row * HD + c * 8));
+    }
+}
+
+}  // namespace
+
+extern "C" sq_status sq_w8a8_attention(const int8_t* q, const int8_t* k, const int8_t* v, float alpha1, float alpha2, void* o,
+                                       sq_dtype out, int64_t b, int64_t s_q, int64_t s_k, int64_t d, int64_t stride_q,
+                                       int64_t stride_k, int64_t stride_v, int64_t stride_o, int8_t* p_codes, void* stream)
+{
+    if (!q || !k || !v || !o) return SQ_ERR_NULL;
+    const int64_t lim = (int64_t)1 << 31;
+    if (b <= 0 || s_q <= 0 || s_k <= 0 || d <= 0 || s_q >= lim || s_k >= lim) return SQ_ERR_SHAPE;
+    const int64_t tiles_m = (s_q + 127) / 128;
+    if (b * tiles_m >= lim) return SQ_ERR_SHAPE;
+    if (stride_q < s_q * d || stride_k < s_k * d || stride_v < s_k * d || stride_o < s_q * d) return SQ_ERR_SHAPE;
+    if (out != SQ_F16 && out != SQ_BF16) return SQ_ERR_UNSUPPORTED;
+    if ((d != 64 && d != 128) || (s_k & 127)) return SQ_ERR_UNSUPPORTED;
+    if (!(alpha1 > 0.0f) || !(alpha1 < __builtin_inff()) || !(alpha2 == alpha2)) return SQ_ERR_UNSUPPORTED;
+    if ((stride_q & 15) || (stride_k & 15) || (stride_v & 15) || (stride_o & 7) || !sq_aligned16(q) || !sq_aligned16(k) ||
+        !sq_aligned16(v) || !sq_aligned16(o) || (p_codes && (reinterpret_cast<uintptr_t>(p_codes) & 3u)))
+        return SQ_ERR_ALIGN;
+    AttnArgs a{};
+    a.Q = q; a.K = k; a.V = v; a.O = o; a.P = p_codes;
+    a.s_q = (int)s_q; a.s_k = (int)s_k; a.tiles_m = (int)tiles_m;
+    a.stride_q = stride_q; a.stride_k = stride_k; a.stride_v = stride_v; a.stride_o = stride_o;
+    a.alpha1 = alpha1; a.alpha2 = alpha2;
+    const dim3 grid((unsigned)(b * tiles_m)), block(256);
+    hipStream_t st = (hipStream_t)stream;
+    if (d == 128) {
+        if (out == SQ_BF16) sq_launch((attn_i8_kernel<true, 128>), grid, block, 0, st, a);
+        else sq_launch((attn_i8_kernel<false, 128>), grid, block, 0, st, a);
+    } else {
+        if (out == SQ_BF16) sq_launch((attn_i8_kernel<true, 64>), grid, block, 0, st, a);
+        else sq_launch((attn_i8_kernel<false, 64>), grid, block, 0, st, a);
+    }
+    return sq_launch_status();
+}

@@ -152,3 +152,16 @@ def test_tiled_layout_plumbing_of_the_tests_is_self_consistent():
         raw[u.tiled_index(rows, k).reshape(-1)] = codes.reshape(-1)
         t = torch.from_numpy(raw.reshape(pad, k))[:rows]
         assert np.array_equal(u.tiled_to_rows(t), codes)
+
+
+def test_fused_attention_argument_errors_before_any_launch():
+    L = sq.lib()
+    fake = 0x1000
+    args = lambda **kw: [kw.get("q", fake), fake, fake, kw.get("a1", 1e-3), 1e-3, fake, 0, 2, 64, kw.get("s_k", 128), kw.get("d", 128),
+                         64 * kw.get("d", 128), kw.get("s_k", 128) * kw.get("d", 128), kw.get("s_k", 128) * kw.get("d", 128),
+                         64 * kw.get("d", 128), None, None]
+    assert L.sq_w8a8_attention(*args(q=None)) == 1
+    assert L.sq_w8a8_attention(*args(s_k=100)) == 4      # key count must be a multiple of 128
+    assert L.sq_w8a8_attention(*args(d=96)) == 4         # head dimension 64 or 128
+    assert L.sq_w8a8_attention(*args(a1=-1.0)) == 4      # alpha1 must be positive
+    assert L.sq_w8a8_attention(*args(q=0x1004)) == 3
