@@ -18,7 +18,7 @@
 // block (h = l >> 5).  That fixes the order of the contraction bytes of the P V MFMA; the V operand is fetched
 // in the same order with the LDS transpose read (ds_read_b64_tr_b8), whose eight source rows are named by the
 // lanes and can therefore be any eight keys.
-// The kernel is bound by the vector ALU (about 22 issue slots per score over both passes against 0.75 MFMA
+// The kernel is bound by the vector ALU (about 21 issue slots per score over both passes against 0.75 MFMA
 // cycles); two workgroups per compute unit let one wave's MFMAs run under the other's exponentials.
 #include "gemm_args.h"
 
@@ -147,6 +147,9 @@ __global__ __launch_bounds__(256, 2) void attn_i8_kernel(const AttnArgs p)
     // score of one accumulator as the 16-bit tensor element it stands for, widened again: round16(fl32(acc * alpha1))
     const float alpha1 = p.alpha1;
     auto s16f = [&](int a) { return load16_bits<BF16>(store16_bits<BF16>((float)a * alpha1)); };
+    // (Both passes must round the scores the same way: where one key dominates a row, l is 1 up to rounding, and a
+    // score that came out one 16-bit ulp lower in pass 1 than in pass 2 would give that key a probability above 1.
+    // A single-rounding v_fma_mixlo_f16 in pass 1 was tried for its one issue slot and did exactly that.)
 
     // ---- pass 1: row maximum m and l = sum e^(s - m), online.  The maximum is taken on the integer accumulators
     // (s is monotone in acc: alpha1 > 0).  A row's scores are split between lanes r and r + 32.
@@ -176,9 +179,9 @@ __global__ __launch_bounds__(256, 2) void attn_i8_kernel(const AttnArgs p)
             for (int v = 0; v < 16; ++v) part += __builtin_amdgcn_exp2f(__builtin_fmaf(s16f(acc[jn][v]), kLog2e, nm));
         l_run += part;
     }
+    // p = e^(s - m) / l = 2^(s log2(e) - (m log2(e) + log2(l))): the division is folded into the exponent
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
-    const float inv = 1.0f / l_tot;
-    const float nm = -m_run * kLog2e;
+    const float nm = -m_run * kLog2e - __builtin_amdgcn_logf(l_tot);
 
     // ---- pass 2: codes and P V.
     v16i acc_o[NB];
@@ -210,8 +213,8 @@ __global__ __launch_bounds__(256, 2) void attn_i8_kernel(const AttnArgs p)
                 uint32_t q[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float ex = __builtin_amdgcn_exp2f(__builtin_fmaf(s16f(acc[ks][4 * g + e]), kLog2e, nm));
-                    const float p16 = load16_bits<BF16>(store16_bits<BF16>(ex * inv));  // the softmax output is a 16-bit tensor
+                    const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s16f(acc[ks][4 * g + e]), kLog2e, nm));
+                    const float p16 = load16_bits<BF16>(store16_bits<BF16>(pr));  // the softmax output is a 16-bit tensor
                     q[e] = __builtin_bit_cast(uint32_t, __builtin_fmaf(p16, 127.0f, 12582912.0f));  // round(127 p16), exact product
                 }
                 fp[g] = (int)pack4_low_bytes(q[0], q[1], q[2], q[3]);

@@ -20,15 +20,16 @@ typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 // mode); bf16 is widened by a shift and narrowed with the integer nearest-even rule.
 SQ_DEVICE float f16_bits_to_f32(uint32_t h) { return (float)__builtin_bit_cast(_Float16, (uint16_t)h); }
 SQ_DEVICE float bf16_bits_to_f32(uint32_t b) { return __builtin_bit_cast(float, b << 16); }
-// The narrowing is an opaque v_cvt_f16_f32: left to the compiler, a multiply or add that feeds a float -> half
-// conversion is merged into v_fma_mixlo_f16, which rounds the exact result once to fp16.  The arithmetic
-// fixed for the outputs is "round to fp32, then round to the 16-bit type"; the two differ whenever the fp32
-// rounding lands on an fp16 tie point (about one output in 2^13).
+// The value is made opaque before it is narrowed: left alone, the compiler merges a multiply or add that feeds a
+// float -> half conversion into v_fma_mixlo_f16, which rounds the exact result once to fp16.  The arithmetic fixed for
+// the outputs is "round to fp32, then round to the 16-bit type"; the two differ whenever the fp32 rounding lands on
+// an fp16 tie point (about one output in 2^13).  (The barrier is an empty asm statement on purpose: the conversion
+// itself stays an instruction the compiler schedules, so it also inserts the wait states the hardware wants between
+// a transcendental result and its use; an asm v_cvt_f16_f32 fed directly by v_exp_f32 read garbage.)
 SQ_DEVICE uint32_t f32_to_f16_bits(float v)
 {
-    uint32_t r;
-    asm("v_cvt_f16_f32 %0, %1" : "=v"(r) : "v"(v));
-    return r & 0xffffu;
+    asm("" : "+v"(v));
+    return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)v);
 }
 SQ_DEVICE uint32_t f32_to_bf16_bits(float v)
 {

@@ -177,6 +177,22 @@ def test_config4_int8_attention_bmms():
         ref = oracle.w8a8_bmm(pq[h:h + 1].cpu().numpy(), codes[2][h:h + 1].cpu().numpy(), False, alpha2, F16)
         assert ulp_distance(bits_from_dev(o[h]), ref[0]).max() <= 1, f"head {h}"
     assert bool(torch.isfinite(o.float()).all())
+    _progress("config 4: the same attention in the fused kernel")
+    pq_f = torch.full_like(pq, -128)
+    o_f = sq.w8a8_attention(codes[0], codes[1], codes[2], alpha1, alpha2, torch.float16, p_codes=pq_f)
+    for h in heads:
+        sc_ref = oracle.w8a8_bmm(codes[0][h:h + 1].cpu().numpy(), codes[1][h:h + 1].cpu().numpy(), True, alpha1, F16)
+        ref = oracle.softmax_quant_p(sc_ref[0], F16).astype(np.int32)
+        got = pq_f[h].cpu().numpy().astype(np.int32)
+        diff = np.abs(got - ref)
+        assert got.min() >= 0 and diff.max() <= 1 and (diff != 0).mean() <= 1e-3, f"fused: codes of head {h}"
+        o_ref = oracle.w8a8_bmm(pq_f[h:h + 1].cpu().numpy(), codes[2][h:h + 1].cpu().numpy(), False, alpha2, F16)
+        assert_identical_16(ulp_distance(bits_from_dev(o_f[h]), o_ref[0]), f"fused: output of head {h}")
+    # against the unfused library chain over all 768 heads: same scores, row sums in another order
+    d_all = (pq_f.view(torch.int8).to(torch.int16) - pq.to(torch.int16)).abs()
+    assert int(d_all.max()) <= 1 and float((d_all != 0).float().mean()) <= 1e-3
+    del d_all
+    assert int(pq_f.min()) >= 0  # every code was written
 
 
 def test_config5_opt66b_decoder_layer_chain():
