@@ -2,6 +2,9 @@
 // (offline, O(C_i)), workspace sizing and the attention BMM dispatcher.
 #include <math.h>
 
+#include <atomic>
+#include <chrono>
+
 #include "common.h"
 
 extern "C" size_t sq_quantize_workspace_bytes(void);
@@ -9,6 +12,13 @@ extern "C" size_t sq_gemm_workspace_bytes(int64_t t, int64_t c_i, int64_t c_o);
 extern "C" sq_status sq_internal_bmm(const int8_t* a, const int8_t* b, int trans_b, float alpha, void* c, sq_dtype out,
                                      int64_t batch, int64_t m, int64_t n, int64_t k, int64_t stride_a, int64_t stride_b,
                                      int64_t stride_c, void* stream);
+
+uint32_t sq_next_ticket()
+{
+    static std::atomic<uint32_t> counter{(uint32_t)std::chrono::steady_clock::now().time_since_epoch().count() * 2654435761u};
+    uint32_t v = counter.fetch_add(1u, std::memory_order_relaxed) + 1u;
+    return v ? v : counter.fetch_add(1u, std::memory_order_relaxed) + 1u;
+}
 
 extern "C" {
 

@@ -95,7 +95,21 @@ SQ_DEVICE float wave_sum(float v)
     return v;
 }
 
+// ---- ticketed 64-bit cells {ticket : value} in caller-owned scratch that nobody clears.  A cell whose upper half is
+// not this call's ticket is stale: the first workgroup that sees it so replaces it by {ticket : 0} (one compare-and-
+// swap; it fails only if another workgroup of the same call was faster, which is just as good).  After that the
+// cell is updated with the hardware's 64-bit add / max, which never touch the ticket half.
+SQ_DEVICE void ticket_open(unsigned long long* cell, uint32_t ticket)
+{
+    unsigned long long v = __hip_atomic_load(cell, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((uint32_t)(v >> 32) != ticket)
+        __hip_atomic_compare_exchange_strong(cell, &v, (unsigned long long)ticket << 32, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // ---- host side
+// Ticket of one call that uses ticketed cells: a per-process counter started from the clock, never 0.
+uint32_t sq_next_ticket();
 static inline bool sq_aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Launch bookkeeping of one entry point, per host thread.  Every kernel of the library is launched through

@@ -16,9 +16,6 @@
 // larger tensors (more workgroups, and the second read served by the memory-side cache anyway), streams under HIP
 // graph capture (a replay would reuse the ticket) and callers with a small workspace get the three-launch version
 // (clear, absmax with atomic max on the float's bit pattern, quantize); results are identical.
-#include <atomic>
-#include <chrono>
-
 #include "common.h"
 
 namespace {
@@ -252,18 +249,6 @@ __global__ __launch_bounds__(256) void quant_per_tensor_kernel(const uint16_t* _
     }
 }
 
-// ---- ticketed 64-bit cells {ticket : value}.  A cell whose upper half is not this call's ticket is stale: the
-// first workgroup that sees it so replaces it by {ticket : 0} (one compare-and-swap; it fails only if another
-// workgroup of the same call was faster, which is just as good).  After that the cell is updated with the
-// hardware's 64-bit add / max, which never touch the ticket half.
-SQ_DEVICE void ticket_open(unsigned long long* cell, uint32_t ticket)
-{
-    unsigned long long v = __hip_atomic_load(cell, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if ((uint32_t)(v >> 32) != ticket)
-        __hip_atomic_compare_exchange_strong(cell, &v, (unsigned long long)ticket << 32, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
-                                             __HIP_MEMORY_SCOPE_AGENT);
-}
-
 constexpr int kO2MaxGrid = 512;  // workgroups of the single-launch kernel (= partial maxima in the workspace)
 
 // Workspace layout: bytes [0, 8) arrival cell {ticket : count}; bytes [256, 256 + 4 * kO2MaxGrid) partial maxima.
@@ -391,14 +376,6 @@ int grid_for(int64_t work_items)
 
 constexpr int kO2NV = 8;  // 16-byte vectors a thread holds: a workgroup covers 256 x 8 x 8 = 16384 elements
 
-// Ticket of one single-launch O2 call: a per-process counter started from the clock, never 0.
-uint32_t next_ticket()
-{
-    static std::atomic<uint32_t> counter{(uint32_t)std::chrono::steady_clock::now().time_since_epoch().count() * 2654435761u};
-    uint32_t v = counter.fetch_add(1u, std::memory_order_relaxed) + 1u;
-    return v ? v : counter.fetch_add(1u, std::memory_order_relaxed) + 1u;
-}
-
 // Largest grid of the single-launch kernel: a quarter of the workgroups the device keeps resident (occupancy x
 // compute units), at most kO2MaxGrid.
 template <bool BF16> int single_launch_grid()
@@ -458,7 +435,7 @@ sq_status sq_quantize_act(const void* x, sq_dtype dtype, int64_t t, int64_t c_i,
         if (hipStreamIsCapturing(st, &cap) != hipSuccess) cap = hipStreamCaptureStatusActive;
         if (cap == hipStreamCaptureStatusNone && nwg <= limit && ws_bytes >= sq_quantize_workspace_bytes() &&
             (reinterpret_cast<uintptr_t>(workspace) & 15u) == 0) {
-            const uint32_t ticket = next_ticket(), spin_limit = 1u << 21;
+            const uint32_t ticket = sq_next_ticket(), spin_limit = 1u << 21;
             if (bf) sq_launch((quant_per_tensor_single_kernel<true, kO2NV>), dim3((unsigned)nwg), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, (unsigned char*)workspace, ticket, spin_limit, xq, tiled);
             else sq_launch((quant_per_tensor_single_kernel<false, kO2NV>), dim3((unsigned)nwg), dim3(256), 0, st, xp, ldx, (int)c_i, t, inv_s, scale, (unsigned char*)workspace, ticket, spin_limit, xq, tiled);
             return sq_launch_status();
