@@ -6,15 +6,22 @@ Workload (N=1): the four OPT-175B-shaped linears at hidden 12288 (QKV 12288->368
 quantization, per-tensor weights, bf16 output.  One step = for each of the four layers:
 quantize_act (fp16 activation -> int8 codes + per-token steps) then w8a8_linear (INT8 MFMA GEMM with
 the dequantizing epilogue fused); int8 operands use the library's tiled layout.  Inputs (activations,
-prepared int8 weights) are resident in HBM
-before the timed region.  Prints ONE JSON line.
+prepared int8 weights) are resident in HBM before the timed region.  Prints ONE JSON line.
+
+Timing protocol: HIP events on the stream the kernels are launched on (torch's current stream is the one the
+binding hands to the library).  Every kernel that is bound by HBM is timed over a rotation of buffer sets that
+together exceed 512 MB, so that the 256 MB memory-side cache cannot serve the same bytes twice; the step itself
+rotates three sets of activations, codes and outputs (3 GB) and streams 1.8 GB of weights.  Per-kernel figures
+are the median (and the minimum) over several batches of launches.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import subprocess
 import sys
+import threading
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -22,21 +29,35 @@ sys.path.insert(0, ROOT)
 
 PEAK_INT8_TOPS = 5000.0  # MI355X dense INT8 MFMA peak, 5.0 POP/s
 PEAK_HBM_GBS = 8000.0
+ROTATE_BYTES = 600 << 20  # a rotation of buffer sets covers at least this much
 
 
-def make_layer(sq, torch, name, t, c_i, c_o, outlier_frac, factor, alpha, smoothed, seed):
-    """Synthetic layer with the paper's outlier structure, prepared offline with the library itself."""
-    g = torch.Generator(device="cuda")
-    g.manual_seed(seed)
+def synth_activation(torch, g, t, c_i, outlier_frac, factor):
+    """fp16 [t, c_i]: N(0,1) with round(outlier_frac * c_i) generator-chosen channels multiplied by `factor`."""
     x = torch.randn((t, c_i), generator=g, device="cuda", dtype=torch.float32)
-    n_out = int(round(outlier_frac * c_i))
-    ch = torch.randperm(c_i, generator=g, device="cuda")[:n_out]
+    ch = torch.randperm(c_i, generator=g, device="cuda")[:int(round(outlier_frac * c_i))]
     x[:, ch] *= factor
-    x = x.to(torch.float16)
+    return x.to(torch.float16), ch
+
+
+def synth_weight(torch, g, c_i, c_o):
     w = torch.empty((c_i, c_o), device="cuda", dtype=torch.float16)
     rows = 2048
     for r0 in range(0, c_i, rows):  # chunked to bound the fp32 temporary
         w[r0:r0 + rows] = (torch.randn((min(rows, c_i - r0), c_o), generator=g, device="cuda") * 0.02).to(torch.float16)
+    return w
+
+
+def make_layer(sq, torch, name, t, c_i, c_o, outlier_frac, factor, alpha, smoothed, seed, out_dtype=None, nsets=1, x=None,
+               relu=False):
+    """Synthetic layer with the paper's outlier structure, prepared offline with the library itself.  `nsets` sets of
+    activations / codes / outputs are kept for rotation; `x` overrides the drawn activation of set 0 (a real
+    producer's output)."""
+    out_dtype = out_dtype or torch.bfloat16
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    x0, ch = synth_activation(torch, g, t, c_i, outlier_frac, factor)
+    w = synth_weight(torch, g, c_i, c_o)
     inv_s_dev = None
     s_dev = None
     if smoothed:
@@ -48,94 +69,158 @@ def make_layer(sq, torch, name, t, c_i, c_o, outlier_frac, factor, alpha, smooth
         s_dev, inv_s_dev = s.cuda(), inv_s.cuda()
     wq, w_scale = sq.prepare_weight(w, s_dev, layout=sq.TILED)
     del w
-    xq = sq.empty_codes(t, c_i, sq.TILED)
-    x_scale = torch.empty(t, dtype=torch.float32, device="cuda")
-    y = torch.empty((t, c_o), dtype=torch.bfloat16, device="cuda")
+    sets = []
+    base = x0 if x is None else x
+    for i in range(nsets):
+        xi = base if i == 0 else base.roll(i, 0)  # the same rows in another order, at other addresses
+        sets.append(dict(x=xi, xq=sq.empty_codes(t, c_i, sq.TILED), x_scale=torch.empty(t, dtype=torch.float32, device="cuda"),
+                         y=torch.empty((t, c_o), dtype=out_dtype, device="cuda")))
     nws = sq.workspace_bytes(sq.OP_W8A8_LINEAR, t, c_i, c_o)
     ws = torch.empty(max(nws, 16), dtype=torch.uint8, device="cuda")
-    return dict(name=name, t=t, c_i=c_i, c_o=c_o, x=x, inv_s=inv_s_dev, wq=wq, w_scale=w_scale, xq=xq, x_scale=x_scale,
-                y=y, ws=ws, ops=2.0 * t * c_i * c_o)
+    return dict(name=name, t=t, c_i=c_i, c_o=c_o, inv_s=inv_s_dev, wq=wq, w_scale=w_scale, sets=sets, ws=ws, relu=relu,
+                out_dtype=out_dtype, ops=2.0 * t * c_i * c_o)
 
 
-def run_layer(sq, torch, L):
-    sq.quantize_act(L["x"], sq.PER_TOKEN_DYNAMIC, inv_s=L["inv_s"], out=(L["xq"], L["x_scale"]), layout=sq.TILED)
-    sq.w8a8_linear(L["xq"], L["x_scale"], L["wq"], L["w_scale"], torch.bfloat16, out=L["y"], workspace=L["ws"], layout=sq.TILED)
+def run_quant(sq, L, i=0):
+    S = L["sets"][i % len(L["sets"])]
+    sq.quantize_act(S["x"], sq.PER_TOKEN_DYNAMIC, inv_s=L["inv_s"], out=(S["xq"], S["x_scale"]), layout=sq.TILED)
 
 
-def _time_us(torch, fn, iters=10, warm=2):
+def run_gemm(sq, L, i=0):
+    S = L["sets"][i % len(L["sets"])]
+    sq.w8a8_linear(S["xq"], S["x_scale"], L["wq"], L["w_scale"], L["out_dtype"], relu=L["relu"], out=S["y"],
+                   workspace=L["ws"], layout=sq.TILED)
+
+
+def time_stats(torch, fn, iters=10, reps=5, warm=2):
+    """fn(i) is launched `iters` times between two events, `reps` times over; returns (median, min) of the batch
+    averages in microseconds.  `i` counts launches, for buffer rotation."""
+    n = 0
     for _ in range(warm):
-        fn()
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a.record()
-    for _ in range(iters):
-        fn()
-    b.record()
-    torch.cuda.synchronize()
-    return a.elapsed_time(b) / iters * 1e3
+        fn(n)
+        n += 1
+    per = []
+    for _ in range(reps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(iters):
+            fn(n)
+            n += 1
+        b.record()
+        torch.cuda.synchronize()
+        per.append(a.elapsed_time(b) / iters * 1e3)
+    per.sort()
+    return per[len(per) // 2], per[0]
+
+
+def nsets_for(bytes_per_set):
+    return max(3, -(-ROTATE_BYTES // int(bytes_per_set)))
 
 
 def other_configs(sq, torch):
-    """Latency and roofline fraction of the other benchmark configurations (synthetic inputs of their shapes):
-    1 = OPT-125m-shaped static linear, 2 = OPT-13B-shaped FFN pair, 4 = INT8 attention BMMs (batch 8 x 96 heads,
+    """Latency and roofline fraction of the other benchmark configurations, on inputs of their kind: activations with
+    outlier channels, smoothing factors on the inputs that follow a LayerNorm, the second FFN layer fed with the first
+    one's ReLU output, Q / K / V codes from per-tensor quantized N(0,1) tensors.
+    1 = OPT-125m-shaped static linear, 2 = OPT-13B-shaped FFN pair, 4 = INT8 attention (batch 8 x 96 heads,
     sequence 2048, head_dim 128), 5 = the linears and attention of an OPT-66B-shaped decoder layer (4 x 1024 tokens)."""
-    g = torch.Generator(device="cuda")
-    g.manual_seed(77)
     out = {}
+    f16 = torch.float16
 
-    def rand16(shape, scale=1.0):
-        return (torch.randn(shape, generator=g, device="cuda") * scale).to(torch.float16)
+    def linear_entry(L, static=False):
+        S0 = L["sets"][0]
+        if static:  # O3: calibrated per-tensor step, pure elementwise quantizer
+            step = torch.empty(1, dtype=torch.float32, device="cuda")
+            sq.quantize_act(S0["x"], sq.PER_TENSOR_DYNAMIC, inv_s=L["inv_s"], out=(S0["xq"], step), layout=sq.TILED)
 
-    def linear_pair(t, c_i, c_o, relu=False, static=False):
-        x = rand16((t, c_i))
-        wq, ws = sq.prepare_weight(rand16((c_i, c_o), 0.02), None, layout=sq.TILED)
-        xq = sq.empty_codes(t, c_i, sq.TILED)
-        xs = torch.empty(1 if static else t, dtype=torch.float32, device="cuda")
-        if static:
-            xs.fill_(float(x.abs().max()) / 127.0)
-        y = torch.empty((t, c_o), dtype=torch.float16, device="cuda")
-        wsp = torch.empty(max(sq.workspace_bytes(sq.OP_W8A8_LINEAR, t, c_i, c_o), 16), dtype=torch.uint8, device="cuda")
-        mode = sq.PER_TENSOR_STATIC if static else sq.PER_TOKEN_DYNAMIC
-        q_us = _time_us(torch, lambda: sq.quantize_act(x, mode, static_scale=xs if static else None, out=(xq, xs), layout=sq.TILED))
-        g_us = _time_us(torch, lambda: sq.w8a8_linear(xq, xs, wq, ws, torch.float16, relu=relu, out=y, workspace=wsp, layout=sq.TILED))
-        ops = 2.0 * t * c_i * c_o
-        return {"quantize_us": round(q_us, 1), "gemm_us": round(g_us, 1), "tops": round(ops / (q_us + g_us) / 1e6, 1),
-                "frac_mfma_peak": round(ops / (q_us + g_us) / 1e6 / PEAK_INT8_TOPS, 4)}
+            def q(i):
+                S = L["sets"][i % len(L["sets"])]
+                sq.quantize_act(S["x"], sq.PER_TENSOR_STATIC, inv_s=L["inv_s"], static_scale=step, out=(S["xq"], step), layout=sq.TILED)
 
-    out["config1_opt125m_static_16x768x3072"] = linear_pair(16, 768, 3072, static=True)
-    out["config2_opt13b_fc1_512x5120x20480_relu"] = linear_pair(512, 5120, 20480, relu=True)
-    out["config2_opt13b_fc2_512x20480x5120"] = linear_pair(512, 20480, 5120)
+            def gm(i):
+                S = L["sets"][i % len(L["sets"])]
+                sq.w8a8_linear(S["xq"], step, L["wq"], L["w_scale"], L["out_dtype"], out=S["y"], workspace=L["ws"], layout=sq.TILED)
+        else:
+            q = lambda i: run_quant(sq, L, i)
+            gm = lambda i: run_gemm(sq, L, i)
+        for i in range(len(L["sets"])):
+            q(i)  # codes of every set exist before the GEMM is timed
+        q_us, q_min = time_stats(torch, q)
+        g_us, g_min = time_stats(torch, gm)
+        ops = L["ops"]
+        return {"quantize_us": round(q_us, 1), "gemm_us": round(g_us, 1), "gemm_us_min": round(g_min, 1),
+                "tops": round(ops / (q_us + g_us) / 1e6, 1), "frac_mfma_peak": round(ops / (q_us + g_us) / 1e6 / PEAK_INT8_TOPS, 4)}
 
-    def attention(bh, s_len, d):
-        q, k, v = (torch.randint(-127, 128, (bh, s_len, d), dtype=torch.int8, device="cuda", generator=g) for _ in range(3))
-        sc = torch.empty((bh, s_len, s_len), dtype=torch.float16, device="cuda")
+    # config 1: 16 tokens, 768 -> 3072, 6 outlier channels x60, alpha 0.5, static per-tensor step
+    L = make_layer(sq, torch, "c1", 16, 768, 3072, 6 / 768, 60.0, 0.5, True, 9001, out_dtype=f16)
+    out["config1_opt125m_static_16x768x3072"] = linear_entry(L, static=True)
+    # config 2: FFN pair at 512 tokens; FC1 smoothed (51 outlier channels x40), FC2 (s = 1) on FC1's ReLU output
+    L1 = make_layer(sq, torch, "c2fc1", 512, 5120, 20480, 0.01, 40.0, 0.5, True, 9002, out_dtype=f16, nsets=3, relu=True)
+    out["config2_opt13b_fc1_512x5120x20480_relu"] = linear_entry(L1)
+    L2 = make_layer(sq, torch, "c2fc2", 512, 20480, 5120, 0.0, 1.0, 0.5, False, 9003, out_dtype=f16, nsets=3,
+                    x=L1["sets"][0]["y"])
+    out["config2_opt13b_fc2_512x20480x5120"] = linear_entry(L2)
+    del L, L1, L2
+
+    def attention(bh, s_len, d, seed):
+        g = torch.Generator(device="cuda")
+        g.manual_seed(seed)
+        codes, steps = [], []
+        for _ in range(3):  # Q, K, V: N(0,1) fp16, per-tensor step amax / 127
+            x = torch.randn((bh * s_len, d), generator=g, device="cuda").to(f16)
+            cq, cs = sq.quantize_act(x, sq.PER_TENSOR_DYNAMIC)
+            codes.append(cq.view(bh, s_len, d))
+            steps.append(float(cs.item()))
+        q, k, v = codes
+        a1, a2 = steps[0] * steps[1] / d ** 0.5, steps[2] / 127.0
+        sc = torch.empty((bh, s_len, s_len), dtype=f16, device="cuda")
         pq = torch.empty((bh, s_len, s_len), dtype=torch.int8, device="cuda")
-        o = torch.empty((bh, s_len, d), dtype=torch.float16, device="cuda")
+        o = torch.empty((bh, s_len, d), dtype=f16, device="cuda")
         # (the first launches after the multi-GB allocations run slower than the steady state: warm up longer)
-        t1 = _time_us(torch, lambda: sq.w8a8_bmm(q, k, True, 2e-5, torch.float16, out=sc), iters=10, warm=5)
-        t2 = _time_us(torch, lambda: sq.softmax_quant_p(sc, out=pq), iters=8, warm=2)
-        t3 = _time_us(torch, lambda: sq.w8a8_bmm(pq, v, False, 1e-4, torch.float16, out=o), iters=8, warm=2)
+        t1, _ = time_stats(torch, lambda i: sq.w8a8_bmm(q, k, True, a1, f16, out=sc), iters=5, reps=3, warm=4)
+        t2, _ = time_stats(torch, lambda i: sq.softmax_quant_p(sc, out=pq), iters=4, reps=3)
+        t3, _ = time_stats(torch, lambda i: sq.w8a8_bmm(pq, v, False, a2, f16, out=o), iters=4, reps=3)
+        tf, tf_min = time_stats(torch, lambda i: sq.w8a8_attention(q, k, v, a1, a2, f16, out=o), iters=4, reps=3)
         b1 = 2.0 * bh * s_len * d + 2.0 * bh * s_len * s_len
         b2 = 3.0 * bh * s_len * s_len
         b3 = bh * s_len * s_len + 3.0 * bh * s_len * d
-        return {"bmm1_us": round(t1, 1), "bmm1_frac_hbm": round(b1 / t1 / 1e3 / PEAK_HBM_GBS, 4),
+        ops = 4.0 * bh * s_len * s_len * d
+        return {"fused_us": round(tf, 1), "fused_us_min": round(tf_min, 1), "fused_tops": round(ops / tf / 1e6, 1),
+                "fused_speedup_vs_chain": round((t1 + t2 + t3) / tf, 3),
+                "chain_us": round(t1 + t2 + t3, 1),
+                "bmm1_us": round(t1, 1), "bmm1_frac_hbm": round(b1 / t1 / 1e3 / PEAK_HBM_GBS, 4),
                 "softmax_quant_us": round(t2, 1), "softmax_frac_hbm": round(b2 / t2 / 1e3 / PEAK_HBM_GBS, 4),
                 "bmm2_us": round(t3, 1), "bmm2_frac_hbm": round(b3 / t3 / 1e3 / PEAK_HBM_GBS, 4),
-                "tops_both_bmms": round(4.0 * bh * s_len * s_len * d / (t1 + t3) / 1e6, 1)}
+                "tops_both_bmms": round(ops / (t1 + t3) / 1e6, 1)}
 
-    out["config4_attention_768x2048x128"] = attention(768, 2048, 128)
-    out["config5_opt66b_qkv_4096x9216x27648"] = linear_pair(4096, 9216, 27648)
-    out["config5_opt66b_out_proj_4096x9216x9216"] = linear_pair(4096, 9216, 9216)
-    out["config5_opt66b_fc1_4096x9216x36864_relu"] = linear_pair(4096, 9216, 36864, relu=True)
-    out["config5_opt66b_fc2_4096x36864x9216"] = linear_pair(4096, 36864, 9216)
-    out["config5_attention_288x1024x128"] = attention(288, 1024, 128)
-    x = rand16((4096, 9216))
-    gamma = torch.ones(9216, device="cuda")
-    beta = torch.zeros(9216, device="cuda")
-    xq = sq.empty_codes(4096, 9216, sq.TILED)
-    xs = torch.empty(4096, dtype=torch.float32, device="cuda")
-    ln_us = _time_us(torch, lambda: sq.ln_quantize(x, gamma, beta, out=(xq, xs), layout=sq.TILED))
-    out["config5_ln_quantize_4096x9216"] = {"us": round(ln_us, 1),
-                                            "frac_hbm": round(3.0 * 4096 * 9216 / ln_us / 1e3 / PEAK_HBM_GBS, 4)}
+    out["config4_attention_768x2048x128"] = attention(768, 2048, 128, 9004)
+    # config 5: OPT-66B-shaped layer, 4 x 1024 tokens, 1 % outlier channels x60, alpha 0.8; QKV and FC1 follow a
+    # LayerNorm (smoothed), out-proj takes the attention output, FC2 the ReLU output of FC1
+    t5, hid, ffn = 4096, 9216, 36864
+    L = make_layer(sq, torch, "c5qkv", t5, hid, 3 * hid, 0.01, 60.0, 0.8, True, 9005, out_dtype=f16, nsets=3)
+    out["config5_opt66b_qkv_4096x9216x27648"] = linear_entry(L)
+    del L
+    L = make_layer(sq, torch, "c5out", t5, hid, hid, 0.0, 1.0, 0.8, False, 9006, out_dtype=f16, nsets=3)
+    out["config5_opt66b_out_proj_4096x9216x9216"] = linear_entry(L)
+    del L
+    L1 = make_layer(sq, torch, "c5fc1", t5, hid, ffn, 0.01, 60.0, 0.8, True, 9007, out_dtype=f16, nsets=3, relu=True)
+    out["config5_opt66b_fc1_4096x9216x36864_relu"] = linear_entry(L1)
+    L2 = make_layer(sq, torch, "c5fc2", t5, ffn, hid, 0.0, 1.0, 0.8, False, 9008, out_dtype=f16, nsets=3, x=L1["sets"][0]["y"])
+    out["config5_opt66b_fc2_4096x36864x9216"] = linear_entry(L2)
+    del L1, L2
+    out["config5_attention_288x1024x128"] = attention(288, 1024, 128, 9009)
+    # LayerNorm with folded smoothing factors + quantization; gamma carries the outlier channels of its output
+    g = torch.Generator(device="cuda")
+    g.manual_seed(9010)
+    n = nsets_for(3 * t5 * hid)
+    xs_in = [torch.randn((t5, hid), generator=g, device="cuda").to(f16) for _ in range(n)]
+    gamma = torch.ones(hid, device="cuda")
+    gamma[torch.randperm(hid, generator=g, device="cuda")[:92]] = 60.0
+    inv = torch.rand(hid, generator=g, device="cuda") + 0.5
+    gamma_f, beta_f = (gamma * inv).contiguous(), (torch.randn(hid, generator=g, device="cuda") * 0.1 * inv).contiguous()
+    outs = [(sq.empty_codes(t5, hid, sq.TILED), torch.empty(t5, dtype=torch.float32, device="cuda")) for _ in range(n)]
+    ln_us, ln_min = time_stats(torch, lambda i: sq.ln_quantize(xs_in[i % n], gamma_f, beta_f, out=outs[i % n], layout=sq.TILED))
+    out["config5_ln_quantize_4096x9216"] = {"us": round(ln_us, 1), "us_min": round(ln_min, 1), "buffer_sets": n,
+                                            "frac_hbm": round(3.0 * t5 * hid / ln_us / 1e3 / PEAK_HBM_GBS, 4)}
     return out
 
 
@@ -162,6 +247,68 @@ def cpu_baseline(layers_desc):
                 sample=f"{rows} of 2048 tokens per layer, all four layers, quantize + int32 GEMM + epilogue; {secs:.1f} s")
 
 
+def power_probe(sq, torch):
+    """Is the prefill GEMM bound by its schedule or by the power the chip may draw?  The same launch (2048 x 12288 ->
+    36864, tiled operands) on operands of different bit activity, with the shader clock sampled (rocm-smi) while the
+    launch repeats for two seconds.  Prints one JSON line."""
+    M, K, N = 2048, 12288, 36864
+    ws1 = torch.full((1,), 0.01, device="cuda")
+    xs = torch.rand(M, device="cuda")
+    y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+
+    def sclk():
+        try:
+            o = subprocess.run(["rocm-smi", "-c", "--json"], capture_output=True, text=True, timeout=20).stdout
+            d = json.loads(o[o.index("{"):])
+            v = next(iter(d.values())).get("sclk clock speed:", "")
+            return int("".join(c for c in v if c.isdigit()))
+        except Exception:
+            return None
+
+    def codes(kind, shape):
+        t = sq.empty_codes(shape[0], shape[1], sq.TILED)
+        base = t._base if t._base is not None else t
+        if kind == "zeros":
+            base.zero_()
+        elif kind == "uniform":
+            base.random_(-127, 128)
+        else:  # Gaussian codes of the given standard deviation (what quantized activations / weights look like)
+            sd = float(kind.split("_")[1])
+            base.copy_((torch.randn(base.shape, device="cuda") * sd).round().clamp(-127, 127).to(torch.int8))
+        return t
+
+    res = {"shape": f"{M}x{K}->{N}", "idle_sclk_mhz": sclk(), "cases": {}}
+    for kind in ("zeros", "gauss_5", "gauss_20", "uniform"):
+        a, b = codes(kind, (M, K)), codes(kind, (N, K))
+        fn = lambda i: sq.w8a8_linear(a, xs, b, ws1, torch.bfloat16, out=y, layout=sq.TILED)
+        stop, samples = [False], []
+
+        def sampler():
+            while not stop[0]:
+                v = sclk()
+                if v:
+                    samples.append(v)
+        th = threading.Thread(target=sampler)
+        th.start()
+        t0, n = time.time(), 0
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        while time.time() - t0 < 2.0:
+            for _ in range(50):
+                fn(n)
+                n += 1
+            torch.cuda.synchronize()
+        e1.record()
+        torch.cuda.synchronize()
+        stop[0] = True
+        th.join()
+        us = e0.elapsed_time(e1) / n * 1e3
+        res["cases"][kind] = {"us": round(us, 1), "tops": round(2.0 * M * N * K / us / 1e6, 1),
+                              "frac_int8_peak": round(2.0 * M * N * K / us / 1e6 / PEAK_INT8_TOPS, 4),
+                              "sclk_mhz_samples": samples[1:6]}
+    print(json.dumps(res))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -169,12 +316,17 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--tokens", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true")
     ap.add_argument("--probe", action="store_true",
                     help="counter probe for rocprofv3 --pmc: a 512 MiB device copy (known size), two steps of the "
                          "workload and two decode steps at 1 / 16 / 128 tokens, nothing timed, no JSON")
     ap.add_argument("--probe-attention", action="store_true",
                     help="counter probe for rocprofv3 --pmc: a 512 MiB device copy, then the INT8 attention chain "
-                         "(scores, softmax + P quantization, P V) at 768 heads x 2048 x 128 twice, nothing timed, no JSON")
+                         "(scores, softmax + P quantization, P V) and the fused kernel at 768 heads x 2048 x 128 twice, "
+                         "nothing timed, no JSON")
+    ap.add_argument("--power-probe", action="store_true",
+                    help="the QKV-shaped GEMM on operands of different bit activity with the shader clock sampled; "
+                         "prints its own JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one MI355X per box); --gpus must be 1. "
@@ -188,11 +340,15 @@ def main():
     sq.lib()  # fail loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.power_probe:
+        power_probe(sq, torch)
+        return
     if args.probe_attention:
         bh, s_len, d = 768, 2048, 128
         g = torch.Generator(device="cuda")
         g.manual_seed(78)
-        q, k, v = (torch.randint(-127, 128, (bh, s_len, d), dtype=torch.int8, device="cuda", generator=g) for _ in range(3))
+        q, k, v = ((torch.randn((bh, s_len, d), generator=g, device="cuda") * 30).round().clamp(-127, 127).to(torch.int8)
+                   for _ in range(3))
         sc = torch.empty((bh, s_len, s_len), dtype=torch.float16, device="cuda")
         pq = torch.empty((bh, s_len, s_len), dtype=torch.int8, device="cuda")
         o = torch.empty((bh, s_len, d), dtype=torch.float16, device="cuda")
@@ -200,28 +356,35 @@ def main():
         dst = torch.empty_like(src)
         for _ in range(2):
             dst.copy_(src)
-            sq.w8a8_bmm(q, k, True, 2e-5, torch.float16, out=sc)
+            sq.w8a8_bmm(q, k, True, 8e-5, torch.float16, out=sc)
             sq.softmax_quant_p(sc, out=pq)
             sq.w8a8_bmm(pq, v, False, 1e-4, torch.float16, out=o)
+            sq.w8a8_attention(q, k, v, 8e-5, 1e-4, torch.float16, out=o)
         torch.cuda.synchronize()
-        print("probe done: copy of %d bytes + 2 attention chains at %d heads x %d x %d" % (src.numel(), bh, s_len, d))
+        print("probe done: copy of %d bytes + 2 x (attention chain, fused attention) at %d heads x %d x %d" % (src.numel(), bh, s_len, d))
         return
     t = args.tokens
     desc = [(l.name, l.c_i, l.c_o) for l in synth.OPT175B_LINEARS]
     layers = []
     for i, (name, c_i, c_o) in enumerate(desc):
         smoothed = name in ("qkv", "fc1")  # inputs that follow a LayerNorm are smoothed; the others use s = 1
-        layers.append(make_layer(sq, torch, name, t, c_i, c_o, 0.005, 80.0, 0.5, smoothed, synth.BASE_SEED + 10 * i))
+        # enough sets that the quantize pass of this layer, timed alone, rotates over more than the cache holds
+        layers.append(make_layer(sq, torch, name, t, c_i, c_o, 0.005, 80.0, 0.5, smoothed, synth.BASE_SEED + 10 * i,
+                                 nsets=nsets_for(3 * t * c_i)))
     torch.cuda.synchronize()
+    step_no = [0]
 
     def step():
+        i = step_no[0]
+        step_no[0] += 1
         for L in layers:
-            run_layer(sq, torch, L)
+            run_quant(sq, L, i)
+            run_gemm(sq, L, i)
 
     def make_decode_step(m):
         bufs = []
         for L in layers:
-            xs_in = L["x"][:m].contiguous()
+            xs_in = L["sets"][0]["x"][:m].contiguous()
             nws = sq.workspace_bytes(sq.OP_W8A8_LINEAR, m, L["c_i"], L["c_o"])
             bufs.append(dict(x=xs_in, xq=sq.empty_codes(m, L["c_i"], sq.TILED),
                              xs=torch.empty(m, dtype=torch.float32, device="cuda"),
@@ -261,22 +424,12 @@ def main():
     total_ops = sum(L["ops"] for L in layers)
     tops = total_ops / (ms_per_step * 1e-3) / 1e12
 
-    # Dominant kernel: the INT8 MFMA GEMM.  Average launch duration measured with events on the stream
-    # the kernels run on (torch's current stream is the one the binding passes to the library).
-    gemm_ms = 0.0
-    quant_ms = 0.0
+    # Dominant kernel: the INT8 MFMA GEMM.  Average launch duration from events on the launch stream, median over
+    # batches; the quantize pass of each layer likewise, rotating over its buffer sets (> 512 MB together).
+    gemm_ms = quant_ms = 0.0
     for L in layers:
-        a, b, c = (torch.cuda.Event(enable_timing=True) for _ in range(3))
-        a.record()
-        for _ in range(args.steps):
-            sq.quantize_act(L["x"], sq.PER_TOKEN_DYNAMIC, inv_s=L["inv_s"], out=(L["xq"], L["x_scale"]), layout=sq.TILED)
-        b.record()
-        for _ in range(args.steps):
-            sq.w8a8_linear(L["xq"], L["x_scale"], L["wq"], L["w_scale"], torch.bfloat16, out=L["y"], workspace=L["ws"], layout=sq.TILED)
-        c.record()
-        torch.cuda.synchronize()
-        L["quant_us"] = a.elapsed_time(b) / args.steps * 1e3
-        L["gemm_us"] = b.elapsed_time(c) / args.steps * 1e3
+        L["quant_us"], L["quant_us_min"] = time_stats(torch, lambda i: run_quant(sq, L, i), iters=args.steps, reps=5)
+        L["gemm_us"], L["gemm_us_min"] = time_stats(torch, lambda i: run_gemm(sq, L, i), iters=args.steps, reps=5)
         gemm_ms += L["gemm_us"] * 1e-3
         quant_ms += L["quant_us"] * 1e-3
     gemm_tops = total_ops / (gemm_ms * 1e-3) / 1e12
@@ -285,24 +438,18 @@ def main():
     # Decode shapes (Sec. 5.3's generation stage): the same four layers at 1 / 16 / 128 tokens.  Every pass streams
     # all 1.8 GB of int8 weights, far more than any cache holds, so each layer's W comes from HBM every time.
     decode = {}
-    for m in (1, 16, 128):
+    for m in (1, 16, 64, 128):
         dstep = make_decode_step(m)
-        for _ in range(args.warmup):
-            dstep()
-        d0, d1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        d0.record()
-        for _ in range(args.steps):
-            dstep()
-        d1.record()
-        torch.cuda.synchronize()
-        dms = d0.elapsed_time(d1) / args.steps
+        d_us, d_min = time_stats(torch, lambda i: dstep(), iters=args.steps, reps=3, warm=args.warmup)
+        dms = d_us * 1e-3
         dbytes = sum(L["c_i"] * L["c_o"] + 4.0 * m * L["c_i"] + 2.0 * m * L["c_o"] for L in layers)
-        decode[f"M{m}"] = {"ms_per_step": round(dms, 4), "achieved_GBs": round(dbytes / dms / 1e6, 1),
+        decode[f"M{m}"] = {"ms_per_step": round(dms, 4), "ms_per_step_min": round(d_min * 1e-3, 4),
+                           "achieved_GBs": round(dbytes / dms / 1e6, 1),
                            "frac_hbm_peak": round(dbytes / dms / 1e6 / PEAK_HBM_GBS, 4),
                            "tops": round(sum(2.0 * m * L["c_i"] * L["c_o"] for L in layers) / dms / 1e9, 2)}
 
     # What the INT8 matrix pipes sustain when fed from registers (no memory traffic), on the codes of this workload:
-    # the nominal peak assumes 2.4 GHz, the chip holds about 1.6 GHz under a sustained MFMA load.
+    # the nominal peak assumes 2.4 GHz, the chip holds less under a sustained MFMA load (power).
     probe_data = layers[0]["wq"]
     probe_data = (probe_data._base if probe_data._base is not None else probe_data).reshape(-1)[: 2048 * 49152]
     probe_iters = 20000
@@ -315,13 +462,18 @@ def main():
     torch.cuda.synchronize()
     mfma_only_tops = probe_ops / (p0.elapsed_time(p1) * 1e-3) / 1e12
 
-    # HBM-side traffic of the GEMM launches: measured separately with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on
-    # `bench.py --probe` (counters cannot be read from inside this process); the summary is kept under profiles/.
+    # HBM-side traffic of the GEMM launches cannot be read from inside this process: it is the figure measured with
+    # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on `bench.py --probe` and stored under profiles/.
     traffic = None
+    traffic_src = None
     tpath = os.path.join(ROOT, "profiles", "gemm_i8_opt175b_M2048_hbm_traffic.json")
     if t == 2048 and os.path.exists(tpath):
         with open(tpath) as fh:
-            traffic = round(json.load(fh)["gemm_traffic_bytes_per_launch_avg"])
+            tj = json.load(fh)
+        traffic = round(tj["gemm_traffic_bytes_per_launch_avg"])
+        traffic_src = ("stored figure, not measured in this run: profiles/gemm_i8_opt175b_M2048_hbm_traffic.json "
+                       "(rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE, on `bench.py --probe`, scaled by the same counters on a "
+                       "512 MiB copy)" + (", library at " + tj["library_commit"] if "library_commit" in tj else ""))
 
     out = {
         "metric": "W8A8 quant+GEMM+dequant TOPS and % INT8 MFMA peak at OPT-175B layer shapes",
@@ -341,25 +493,30 @@ def main():
         "pct_int8_mfma_peak": round(100.0 * tops / PEAK_INT8_TOPS, 2),
         "roofline": {"bound": "mfma", "kernel": "gemm_i8_kernel (256x384 / 256x256 tiles, INT8 MFMA GEMM + dequant epilogue)",
                      "achieved": round(gemm_tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s",
-                     "frac": round(gemm_tops / PEAK_INT8_TOPS, 4), "traffic": traffic,
+                     "frac": round(gemm_tops / PEAK_INT8_TOPS, 4), "traffic": traffic, "traffic_source": traffic_src,
                      "mfma_only_loop_tops": round(mfma_only_tops, 1),
                      "frac_of_mfma_only_loop": round(gemm_tops / mfma_only_tops, 4),
                      "note": "int8 multiply-accumulate counted as 2 ops; achieved = sum of 2*T*C_i*C_o over the four "
-                             "layers / sum of their average GEMM launch durations (HIP events); traffic = HBM-side "
-                             "bytes (FETCH_SIZE + WRITE_SIZE, calibrated on a copy) averaged over the four launches; "
+                             "layers / sum of their median GEMM launch durations (HIP events on the launch stream); "
                              "mfma_only_loop_tops = register-fed MFMA loop on the same weight codes, 2048 workgroups x 8 "
-                             "waves (what the matrix pipes sustain at the clock the chip holds under this load)"},
-        "per_layer_us": {L["name"]: {"quantize": round(L["quant_us"], 1), "gemm": round(L["gemm_us"], 1),
+                             "waves: what the matrix pipes sustain at the clock the chip holds under this load (the "
+                             "clock is set by the power the operands' bit activity draws: `bench.py --power-probe`)"},
+        "per_layer_us": {L["name"]: {"quantize": round(L["quant_us"], 1), "quantize_min": round(L["quant_us_min"], 1),
+                                     "quantize_buffer_sets": len(L["sets"]),
+                                     "quantize_GBs": round((3.0 * L["t"] * L["c_i"] + 4.0 * L["t"]) / L["quant_us"] / 1e3, 1),
+                                     "gemm": round(L["gemm_us"], 1), "gemm_min": round(L["gemm_us_min"], 1),
                                      "gemm_tops": round(L["ops"] / L["gemm_us"] / 1e6, 1)} for L in layers},
         "quantize_pass": {"bound": "hbm", "achieved_GBs": round(quant_bytes / (quant_ms * 1e-3) / 1e9, 1),
-                          "peak_GBs": PEAK_HBM_GBS, "frac": round(quant_bytes / (quant_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
+                          "peak_GBs": PEAK_HBM_GBS, "frac": round(quant_bytes / (quant_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                          "note": "each layer's launch rotates over buffer sets of more than 512 MB together"},
     }
     out["decode"] = {"bound": "hbm", "peak_GBs": PEAK_HBM_GBS,
                      "note": "same four layers, quantize + linear per layer, bytes = int8 W + fp16 x in + codes out/in + "
                              "bf16 y out; weights stream from HBM on every pass (1.8 GB per pass)", **decode}
     layers.clear()
     torch.cuda.empty_cache()
-    out["other_configs"] = other_configs(sq, torch)
+    if not args.no_other_configs:
+        out["other_configs"] = other_configs(sq, torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(desc)
     print(json.dumps(out))
