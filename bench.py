@@ -19,7 +19,6 @@ from __future__ import annotations
 import argparse
 import json
 import os
-import subprocess
 import sys
 import threading
 import time
@@ -247,23 +246,36 @@ def cpu_baseline(layers_desc):
                 sample=f"{rows} of 2048 tokens per layer, all four layers, quantize + int32 GEMM + epilogue; {secs:.1f} s")
 
 
-def power_probe(sq, torch):
+def power_probe(sq, torch, seconds=2.0):
     """Is the prefill GEMM bound by its schedule or by the power the chip may draw?  The same launch (2048 x 12288 ->
     36864, tiled operands) on operands of different bit activity, with the shader clock sampled (rocm-smi) while the
-    launch repeats for two seconds.  Prints one JSON line."""
+    launch repeats for `seconds`.  Prints one JSON line."""
     M, K, N = 2048, 12288, 36864
     ws1 = torch.full((1,), 0.01, device="cuda")
     xs = torch.rand(M, device="cuda")
     y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
 
     def sclk():
-        try:
-            o = subprocess.run(["rocm-smi", "-c", "--json"], capture_output=True, text=True, timeout=20).stdout
-            d = json.loads(o[o.index("{"):])
-            v = next(iter(d.values())).get("sclk clock speed:", "")
-            return int("".join(c for c in v if c.isdigit()))
-        except Exception:
-            return None
+        """Current shader clock in MHz from sysfs (no child process: nothing may exec once the GPU is initialised)."""
+        import glob
+        for path in sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk")):
+            try:
+                for line in open(path).read().splitlines():
+                    if line.rstrip().endswith("*"):
+                        return int("".join(c for c in line.split(":")[1] if c.isdigit()))
+            except Exception:
+                pass
+        return None
+
+    def watts(name="power1_input"):
+        """Socket power (or its cap) in watts from the hwmon sensor, None if the box does not expose it."""
+        import glob
+        for path in sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/" + name)):
+            try:
+                return round(int(open(path).read().strip()) / 1e6, 1)
+            except Exception:
+                pass
+        return None
 
     def codes(kind, shape):
         t = sq.empty_codes(shape[0], shape[1], sq.TILED)
@@ -277,23 +289,27 @@ def power_probe(sq, torch):
             base.copy_((torch.randn(base.shape, device="cuda") * sd).round().clamp(-127, 127).to(torch.int8))
         return t
 
-    res = {"shape": f"{M}x{K}->{N}", "idle_sclk_mhz": sclk(), "cases": {}}
+    res = {"shape": f"{M}x{K}->{N}", "idle_sclk_mhz": sclk(), "idle_watts": watts(), "power_cap_watts": watts("power1_cap"),
+           "cases": {}}
     for kind in ("zeros", "gauss_5", "gauss_20", "uniform"):
         a, b = codes(kind, (M, K)), codes(kind, (N, K))
         fn = lambda i: sq.w8a8_linear(a, xs, b, ws1, torch.bfloat16, out=y, layout=sq.TILED)
-        stop, samples = [False], []
+        stop, samples, power = [False], [], []
 
         def sampler():
             while not stop[0]:
-                v = sclk()
+                v, w = sclk(), watts()
                 if v:
                     samples.append(v)
+                if w:
+                    power.append(w)
+                time.sleep(0.05)
         th = threading.Thread(target=sampler)
         th.start()
         t0, n = time.time(), 0
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        while time.time() - t0 < 2.0:
+        while time.time() - t0 < seconds:
             for _ in range(50):
                 fn(n)
                 n += 1
@@ -305,7 +321,8 @@ def power_probe(sq, torch):
         us = e0.elapsed_time(e1) / n * 1e3
         res["cases"][kind] = {"us": round(us, 1), "tops": round(2.0 * M * N * K / us / 1e6, 1),
                               "frac_int8_peak": round(2.0 * M * N * K / us / 1e6 / PEAK_INT8_TOPS, 4),
-                              "sclk_mhz_samples": samples[1:6]}
+                              "sclk_mhz_last": samples[-1] if samples else None, "sclk_mhz_samples": samples[1:6],
+                              "watts_last": power[-1] if power else None, "watts_max": max(power) if power else None}
     print(json.dumps(res))
 
 
@@ -324,6 +341,7 @@ def main():
                     help="counter probe for rocprofv3 --pmc: a 512 MiB device copy, then the INT8 attention chain "
                          "(scores, softmax + P quantization, P V) and the fused kernel at 768 heads x 2048 x 128 twice, "
                          "nothing timed, no JSON")
+    ap.add_argument("--power-probe-seconds", type=float, default=2.0)
     ap.add_argument("--power-probe", action="store_true",
                     help="the QKV-shaped GEMM on operands of different bit activity with the shader clock sampled; "
                          "prints its own JSON line")
@@ -341,7 +359,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     if args.power_probe:
-        power_probe(sq, torch)
+        power_probe(sq, torch, args.power_probe_seconds)
         return
     if args.probe_attention:
         bh, s_len, d = 768, 2048, 128
