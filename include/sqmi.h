@@ -197,7 +197,7 @@ sq_status sq_w8a8_bmm(const int8_t* a, const int8_t* bm, int trans_b, float alph
  * Batch strides in elements (multiples of 16 for q, k, v, of 8 for o).
  * p_codes: NULL, or device int8 [b, s_q, s_k] (4-byte aligned) that receives the codes pq the kernel formed
  * (inspection and tests; costs their write).
- * Limits: d = 64 or 128 and s_k % 128 == 0 (else SQ_ERR_UNSUPPORTED: use the three calls above); any s_q.
+ * Limits: d = 64 or 128 (else SQ_ERR_UNSUPPORTED: use the three calls above); s_k % 16 == 0 (SQ_ERR_ALIGN); any s_q.
  * Needs no workspace. */
 sq_status sq_w8a8_attention(const int8_t* q, const int8_t* k, const int8_t* v, float alpha1, float alpha2,
                             void* o, sq_dtype out, int64_t b, int64_t s_q, int64_t s_k, int64_t d,
@@ -221,13 +221,6 @@ sq_status sq_softmax_quant_p(const void* s, sq_dtype dtype, int64_t rows, int64_
 sq_status sq_ln_quantize(const void* x, sq_dtype dtype, int64_t t, int64_t c_i, const float* gamma_f,
                          const float* beta_f, float eps, float* scale, int8_t* xq, sq_layout xq_layout,
                          void* stream);
-
-/* Measurement aid, not part of the method: runs `iters` rounds of 8 register-fed INT8 MFMAs (32x32x32) on each of
- * the 8 waves of `workgroups` workgroups, i.e. workgroups * 8 * iters * 8 * 65536 integer operations, with no
- * memory traffic inside the loop.  The operand registers are filled once from `data` (device int8, at least
- * workgroups * 49152 bytes: the bit patterns matter, the sustained clock depends on them); sink: device int32
- * [workgroups * 512], overwritten.  bench.py times it to report the GEMM against what the matrix pipes sustain. */
-sq_status sq_probe_mfma_i8(const int8_t* data, size_t data_bytes, int workgroups, int iters, int32_t* sink, void* stream);
 
 /* Workspace size in bytes for `op` at the given problem size (0 if none is needed).  For
  * SQ_OP_W8A8_BMM pass (m, k, n) as (t, c_i, c_o). */

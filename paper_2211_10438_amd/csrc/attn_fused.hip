@@ -20,6 +20,8 @@
 // lanes and can therefore be any eight keys.
 // The kernel is bound by the vector ALU (about 21 issue slots per score over both passes against 0.75 MFMA
 // cycles); two workgroups per compute unit let one wave's MFMAs run under the other's exponentials.
+#include <type_traits>
+
 #include "gemm_args.h"
 
 namespace {
@@ -37,7 +39,9 @@ struct AttnArgs {
 
 constexpr float kLog2e = 1.44269504088896340736f;
 
-template <bool BF16, int HD>
+// TAIL: the key count is not a multiple of 128 (the last tile is masked at 16-key granularity); a separate
+// instantiation, so that the common case carries no mask tests (with both forms in one kernel the register allocation spilled).
+template <bool BF16, int HD, bool TAIL>
 __global__ __launch_bounds__(256, 2) void attn_i8_kernel(const AttnArgs p)
 {
     constexpr int TK = 128;               // keys per tile
@@ -68,33 +72,43 @@ __global__ __launch_bounds__(256, 2) void attn_i8_kernel(const AttnArgs p)
     }
     const int batch = (int)(pid / p.tiles_m);
     const int m0 = (int)(pid - (int64_t)batch * p.tiles_m) * 128;
-    const int nt = p.s_k / TK;
+    const int nt = (p.s_k + TK - 1) / TK;
+    const int last16 = (p.s_k - (nt - 1) * TK) >> 4;  // valid 16-key groups of the last tile (8 = full; s_k % 16 == 0)
 
     // ---- LDS images.  K tile: row n at n * HD, its 16-byte chunks XOR-permuted (position = chunk ^ swzK(n)) so
     // that the operand reads (32 rows, one chunk) spread over the banks.  V tile: row k at k * HD, position =
     // chunk ^ swzV(k), chosen so that the eight rows of one transpose read sit at eight different positions.
     auto swzK = [](int r) { return HD == 128 ? (r & 7) : (((r >> 1) & 3) ^ ((r >> 3) & 1)); };
     auto swzV = [](int k) { return HD == 128 ? ((k & 3) | (((k >> 3) & 1) << 2)) : (k & 3); };
-    uint32_t srcK[LPT], srcV[LPT];
+    // Key rows past s_k (last, partial tile) re-read row s_k - 1: their scores are masked below and their V rows meet
+    // codes that are zero.
+    int lrow[LPT];
+    uint32_t cK[LPT], cV[LPT];
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
         const int row = (i * 4 + wave) * RPB + lane / CH, pos = lane % CH;
-        srcK[i] = (uint32_t)(row * HD + ((pos ^ swzK(row)) * 16));
-        srcV[i] = (uint32_t)(row * HD + ((pos ^ swzV(row)) * 16));
+        lrow[i] = row;
+        cK[i] = (uint32_t)((pos ^ swzK(row)) * 16);
+        cV[i] = (uint32_t)((pos ^ swzV(row)) * 16);
     }
     const int8_t* Kb = p.K + (int64_t)batch * p.stride_k;
     const int8_t* Vb = p.V + (int64_t)batch * p.stride_v;
     auto issue = [&](int j, int stage, bool with_v) {
-        const int8_t* kt = Kb + (int64_t)j * TILE;
         char* dk = smem + (2 * stage) * SLOT;
+        int64_t roff[LPT];
+#pragma unroll
+        for (int i = 0; i < LPT; ++i) {
+            int r = j * TK + lrow[i];
+            r = r < p.s_k ? r : p.s_k - 1;
+            roff[i] = (int64_t)r * HD;
+        }
 #pragma unroll
         for (int i = 0; i < LPT; ++i)
-            __builtin_amdgcn_global_load_lds(GPTR(kt + srcK[i]), LPTR(dk + (i * 4 + wave) * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(GPTR(Kb + roff[i] + cK[i]), LPTR(dk + (i * 4 + wave) * 1024), 16, 0, 0);
         if (with_v) {
-            const int8_t* vt = Vb + (int64_t)j * TILE;
 #pragma unroll
             for (int i = 0; i < LPT; ++i)
-                __builtin_amdgcn_global_load_lds(GPTR(vt + srcV[i]), LPTR(dk + SLOT + (i * 4 + wave) * 1024), 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(GPTR(Vb + roff[i] + cV[i]), LPTR(dk + SLOT + (i * 4 + wave) * 1024), 16, 0, 0);
         }
     };
 
@@ -154,18 +168,18 @@ __global__ __launch_bounds__(256, 2) void attn_i8_kernel(const AttnArgs p)
     // ---- pass 1: row maximum m and l = sum e^(s - m), online.  The maximum is taken on the integer accumulators
     // (s is monotone in acc: alpha1 > 0).  A row's scores are split between lanes r and r + 32.
     float m_run = -__builtin_inff(), l_run = 0.0f;
-    issue(0, 0, false);
-    for (int j = 0; j < nt; ++j) {
-        wait_vmcnt_imm<0>();           // this wave's part of tile j has landed
-        __builtin_amdgcn_s_barrier();  // ... everybody's has, and everybody is done with tile j - 1
-        if (j + 1 < nt) issue(j + 1, (j + 1) & 1, false);
+    // MASK: a 16-key group q = 2 jn + (v >> 3) of the tile is valid when q < tail16 (8 for every tile but the last) (uniform over the wave: the accumulator registers 8 (q & 1) .. 8 (q & 1) + 7 of block jn)
+    auto pass1_tile = [&](const char* kt, int tail16) {
+        constexpr bool MASK = TAIL;
         v16i acc[4];
-        scores(smem + (2 * (j & 1)) * SLOT, acc);
-        int imax = acc[0][0];
+        scores(kt, acc);
+        int imax = acc[0][0];  // (key 0 of a tile is always valid)
 #pragma unroll
-        for (int jn = 0; jn < 4; ++jn)
+        for (int q = 0; q < 8; ++q) {
+            if (MASK && q >= tail16) continue;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) imax = acc[jn][v] > imax ? acc[jn][v] : imax;
+            for (int v = 0; v < 8; ++v) imax = acc[q >> 1][8 * (q & 1) + v] > imax ? acc[q >> 1][8 * (q & 1) + v] : imax;
+        }
         const int other = __shfl_xor(imax, 32, 64);
         imax = other > imax ? other : imax;
         const float m_new = __builtin_fmaxf(m_run, s16f(imax));
@@ -174,10 +188,21 @@ __global__ __launch_bounds__(256, 2) void attn_i8_kernel(const AttnArgs p)
         const float nm = -m_new * kLog2e;
         float part = 0.0f;
 #pragma unroll
-        for (int jn = 0; jn < 4; ++jn)
+        for (int q = 0; q < 8; ++q) {
+            if (MASK && q >= tail16) continue;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) part += __builtin_amdgcn_exp2f(__builtin_fmaf(s16f(acc[jn][v]), kLog2e, nm));
+            for (int v = 0; v < 8; ++v)
+                part += __builtin_amdgcn_exp2f(__builtin_fmaf(s16f(acc[q >> 1][8 * (q & 1) + v]), kLog2e, nm));
+        }
         l_run += part;
+    };
+    issue(0, 0, false);
+    for (int j = 0; j < nt; ++j) {
+        wait_vmcnt_imm<0>();           // this wave's part of tile j has landed
+        __builtin_amdgcn_s_barrier();  // ... everybody's has, and everybody is done with tile j - 1
+        if (j + 1 < nt) issue(j + 1, (j + 1) & 1, false);
+        const char* kt1 = smem + (2 * (j & 1)) * SLOT;
+        pass1_tile(kt1, j == nt - 1 ? last16 : 8);
     }
     // p = e^(s - m) / l = 2^(s log2(e) - (m log2(e) + log2(l))): the division is folded into the exponent
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -194,22 +219,22 @@ __global__ __launch_bounds__(256, 2) void attn_i8_kernel(const AttnArgs p)
         const int row = m0 + wave * 32 + r32;
         if (row < p.s_q) Prow = p.P + ((int64_t)batch * p.s_q + row) * (int64_t)p.s_k + 4 * h;
     }
-    __syncthreads();  // every wave is done with the last tile of pass 1 before its buffer is refilled
-    issue(0, 0, true);
-    for (int j = 0; j < nt; ++j) {
-        wait_vmcnt_imm<0>();
-        __builtin_amdgcn_s_barrier();
-        if (j + 1 < nt) issue(j + 1, (j + 1) & 1, true);
-        const char* kt = smem + (2 * (j & 1)) * SLOT;
+    auto pass2_tile = [&](const char* kt, int j, int tail16) {
+        constexpr bool MASK = TAIL;
         const char* vt = kt + SLOT;
         v16i acc[4];
         scores(kt, acc);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
+            if (MASK && 2 * ks >= tail16) break;  // no valid key in this block or the following ones
             // the 16 codes of this lane for key block ks: word g holds columns 8g + 4h + 0..3
             v4i fp;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
+                if (MASK && 2 * ks + (g >> 1) >= tail16) {  // masked keys: probability 0
+                    fp[g] = 0;
+                    continue;
+                }
                 uint32_t q[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -221,12 +246,22 @@ __global__ __launch_bounds__(256, 2) void attn_i8_kernel(const AttnArgs p)
             }
             if (Prow) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) *(int*)(Prow + j * TK + ks * 32 + 8 * g) = fp[g];
+                for (int g = 0; g < 4; ++g)
+                    if (!MASK || 2 * ks + (g >> 1) < tail16) *(int*)(Prow + j * TK + ks * 32 + 8 * g) = fp[g];
             }
 #pragma unroll
             for (int jn = 0; jn < NB; ++jn)
                 acc_o[jn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(v_frag(vt, ks, jn), fp, acc_o[jn], 0, 0, 0);
         }
+    };
+    __syncthreads();  // every wave is done with the last tile of pass 1 before its buffer is refilled
+    issue(0, 0, true);
+    for (int j = 0; j < nt; ++j) {
+        wait_vmcnt_imm<0>();
+        __builtin_amdgcn_s_barrier();
+        if (j + 1 < nt) issue(j + 1, (j + 1) & 1, true);
+        const char* kt2 = smem + (2 * (j & 1)) * SLOT;
+        pass2_tile(kt2, j, j == nt - 1 ? last16 : 8);
     }
 
     // ---- epilogue: o = round16(fl32(acc * alpha2)).  Accumulator block jn is the transposed output block: lane l,
@@ -270,7 +305,8 @@ extern "C" sq_status sq_w8a8_attention(const int8_t* q, const int8_t* k, const i
     if (b * tiles_m >= lim) return SQ_ERR_SHAPE;
     if (stride_q < s_q * d || stride_k < s_k * d || stride_v < s_k * d || stride_o < s_q * d) return SQ_ERR_SHAPE;
     if (out != SQ_F16 && out != SQ_BF16) return SQ_ERR_UNSUPPORTED;
-    if ((d != 64 && d != 128) || (s_k & 127)) return SQ_ERR_UNSUPPORTED;
+    if (d != 64 && d != 128) return SQ_ERR_UNSUPPORTED;
+    if (s_k & 15) return SQ_ERR_ALIGN;
     if (!(alpha1 > 0.0f) || !(alpha1 < __builtin_inff()) || !(alpha2 == alpha2)) return SQ_ERR_UNSUPPORTED;
     if ((stride_q & 15) || (stride_k & 15) || (stride_v & 15) || (stride_o & 7) || !sq_aligned16(q) || !sq_aligned16(k) ||
         !sq_aligned16(v) || !sq_aligned16(o) || (p_codes && (reinterpret_cast<uintptr_t>(p_codes) & 3u)))
@@ -282,12 +318,17 @@ extern "C" sq_status sq_w8a8_attention(const int8_t* q, const int8_t* k, const i
     a.alpha1 = alpha1; a.alpha2 = alpha2;
     const dim3 grid((unsigned)(b * tiles_m)), block(256);
     hipStream_t st = (hipStream_t)stream;
+    const bool tail = (s_k & 127) != 0;
+#define SQ_ATTN(BF, HD)                                                                        \
+    do {                                                                                       \
+        if (tail) sq_launch((attn_i8_kernel<BF, HD, true>), grid, block, 0, st, a);            \
+        else sq_launch((attn_i8_kernel<BF, HD, false>), grid, block, 0, st, a);                \
+    } while (0)
     if (d == 128) {
-        if (out == SQ_BF16) sq_launch((attn_i8_kernel<true, 128>), grid, block, 0, st, a);
-        else sq_launch((attn_i8_kernel<false, 128>), grid, block, 0, st, a);
+        if (out == SQ_BF16) SQ_ATTN(true, 128); else SQ_ATTN(false, 128);
     } else {
-        if (out == SQ_BF16) sq_launch((attn_i8_kernel<true, 64>), grid, block, 0, st, a);
-        else sq_launch((attn_i8_kernel<false, 64>), grid, block, 0, st, a);
+        if (out == SQ_BF16) SQ_ATTN(true, 64); else SQ_ATTN(false, 64);
     }
+#undef SQ_ATTN
     return sq_launch_status();
 }

@@ -3,6 +3,7 @@
 // against this figure next to the nominal peak, because under a sustained MFMA load the shader clock drops
 // well below the 2.4 GHz the nominal 5.0 POP/s assumes.
 #include "common.h"
+#include "sqmi_probe.h"
 
 namespace {
 

@@ -14,7 +14,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "sqmi.h")).read()
+    import glob
+    text = "".join(open(h).read() for h in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(sq_[a-z0-9_]+)\s*\(", text)))
 
@@ -161,7 +162,7 @@ def test_fused_attention_argument_errors_before_any_launch():
                          64 * kw.get("d", 128), kw.get("s_k", 128) * kw.get("d", 128), kw.get("s_k", 128) * kw.get("d", 128),
                          64 * kw.get("d", 128), None, None]
     assert L.sq_w8a8_attention(*args(q=None)) == 1
-    assert L.sq_w8a8_attention(*args(s_k=100)) == 4      # key count must be a multiple of 128
+    assert L.sq_w8a8_attention(*args(s_k=100)) == 3      # key count must be a multiple of 16
     assert L.sq_w8a8_attention(*args(d=96)) == 4         # head dimension 64 or 128
     assert L.sq_w8a8_attention(*args(a1=-1.0)) == 4      # alpha1 must be positive
     assert L.sq_w8a8_attention(*args(q=0x1004)) == 3

@@ -23,7 +23,9 @@ def _codes(shape, seed):
     return np.clip(np.rint(x / delta), -127, 127).astype(np.int8), delta
 
 
-CASES = [(2, 128, 128, 128), (3, 300, 384, 128), (2, 33, 256, 64), (5, 257, 640, 64), (1, 1, 128, 128), (4, 512, 1024, 128)]
+# key counts that are not multiples of the 128-key tile exercise the masked last tile (16-key granularity)
+CASES = [(2, 128, 128, 128), (3, 300, 384, 128), (2, 33, 256, 64), (5, 257, 640, 64), (1, 1, 128, 128), (4, 512, 1024, 128),
+         (3, 130, 400, 128), (2, 64, 48, 64), (2, 200, 144, 128), (1, 40, 16, 128), (2, 96, 1008, 64)]
 
 
 @pytest.mark.parametrize("b,s_q,s_k,d", CASES)

@@ -83,3 +83,33 @@ def test_graph_replay_attention_chain():
         torch.cuda.synchronize()
         assert torch.equal(got, o) and torch.equal(got_p, pq), f"replay {i} differs from the eager result"
         assert float(o.float().abs().max()) > 0.0
+
+
+def test_graph_replay_fused_attention():
+    """The fused attention kernel captured as a graph node, replayed on changing inputs (key count with a masked tail)."""
+    b, s_q, s_k, d = 5, 200, 400, 128
+    print(f"[case] graph replay fused attention b={b} s_q={s_q} s_k={s_k} d={d}", flush=True)
+    hosts = [[synth.int8_codes((b, n, d), 7100 + 10 * i + j) for j, n in enumerate((s_q, s_k, s_k))] for i in range(3)]
+    q, k, v = (dev(hosts[0][j]).clone() for j in range(3))
+    o = torch.empty((b, s_q, d), dtype=torch.float16, device="cuda")
+
+    def step():
+        sq.w8a8_attention(q, k, v, 3e-4, 1e-3, torch.float16, out=o)
+
+    step()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for i in range(3):
+        for t, h in zip((q, k, v), hosts[i]):
+            t.copy_(dev(h))
+        o.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        got = o.clone()
+        o.zero_()
+        step()
+        torch.cuda.synchronize()
+        assert torch.equal(got, o), f"replay {i} differs from the eager result"
+        assert float(o.float().abs().max()) > 0.0

@@ -62,10 +62,10 @@ def test_quantize_per_tensor(mode, t, c_i, dtype):
 
 @pytest.mark.parametrize("t,c_i,ldx", [(7, 64, 64), (1000, 4096, 4096), (2500, 9216, 9216), (3000, 4096, 12288)])
 def test_quantize_per_tensor_dynamic_single_launch(t, c_i, ldx):
-    """Table 2's O2 (one dynamic step for the whole tensor) in one launch: tensors that fit the registers of the
-    running workgroups (first two cases), tensors beyond that (23 M elements: the remainder is read twice) and a
-    column slice of a wider matrix.  Checked against the oracle, and against the library's three-launch version,
-    which a caller selects by passing a workspace too small for the kernel's three cells."""
+    """Table 2's O2 (one dynamic step for the whole tensor): tensors that fit the registers of up to 512 workgroups run
+    as one launch (first two cases), larger ones (23 M elements) and the last case as three; a column slice of a wider
+    matrix is among them.  Checked against the oracle, and against the library's three-launch version, which a caller
+    selects by passing a workspace too small for the single launch's arrival cell and partial maxima."""
     _progress(f"O2 single launch t={t} c_i={c_i} ldx={ldx}")
     full = synth.normal_fp16((t, ldx), 2100 + t)
     full[t // 2, c_i // 3] = np.float16(9.5)  # a unique maximum somewhere in the middle
