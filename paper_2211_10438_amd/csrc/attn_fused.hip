@@ -161,6 +161,12 @@ __global__ __launch_bounds__(256, 2) void attn_i8_kernel(const AttnArgs p)
     // score of one accumulator as the 16-bit tensor element it stands for, widened again: round16(fl32(acc * alpha1))
     const float alpha1 = p.alpha1;
     auto s16f = [&](int a) { return load16_bits<BF16>(store16_bits<BF16>((float)a * alpha1)); };
+    // two scores at once: one narrowing instruction for the pair
+    auto s16f2 = [&](int a0, int a1, float& s0, float& s1) {
+        const uint32_t h = store16x2_bits<BF16>((float)a0 * alpha1, (float)a1 * alpha1);
+        s0 = load16_bits<BF16>(h);
+        s1 = load16_bits<BF16>(h >> 16);
+    };
     // (Both passes must round the scores the same way: where one key dominates a row, l is 1 up to rounding, and a
     // score that came out one 16-bit ulp lower in pass 1 than in pass 2 would give that key a probability above 1.
     // A single-rounding v_fma_mixlo_f16 in pass 1 was tried for its one issue slot and did exactly that.)
@@ -191,8 +197,12 @@ __global__ __launch_bounds__(256, 2) void attn_i8_kernel(const AttnArgs p)
         for (int q = 0; q < 8; ++q) {
             if (MASK && q >= tail16) continue;
 #pragma unroll
-            for (int v = 0; v < 8; ++v)
-                part += __builtin_amdgcn_exp2f(__builtin_fmaf(s16f(acc[q >> 1][8 * (q & 1) + v]), kLog2e, nm));
+            for (int v = 0; v < 8; v += 2) {
+                float s0, s1;
+                s16f2(acc[q >> 1][8 * (q & 1) + v], acc[q >> 1][8 * (q & 1) + v + 1], s0, s1);
+                part += __builtin_amdgcn_exp2f(__builtin_fmaf(s0, kLog2e, nm));
+                part += __builtin_amdgcn_exp2f(__builtin_fmaf(s1, kLog2e, nm));
+            }
         }
         l_run += part;
     };
@@ -237,10 +247,15 @@ __global__ __launch_bounds__(256, 2) void attn_i8_kernel(const AttnArgs p)
                 }
                 uint32_t q[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(s16f(acc[ks][4 * g + e]), kLog2e, nm));
-                    const float p16 = load16_bits<BF16>(store16_bits<BF16>(pr));  // the softmax output is a 16-bit tensor
-                    q[e] = __builtin_bit_cast(uint32_t, __builtin_fmaf(p16, 127.0f, 12582912.0f));  // round(127 p16), exact product
+                for (int e = 0; e < 4; e += 2) {
+                    float s0, s1;
+                    s16f2(acc[ks][4 * g + e], acc[ks][4 * g + e + 1], s0, s1);
+                    const float pr0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s0, kLog2e, nm));
+                    const float pr1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s1, kLog2e, nm));
+                    const uint32_t ph = store16x2_bits<BF16>(pr0, pr1);  // the softmax output is a 16-bit tensor
+                    // round(127 p16): the product is exact in fp32, the add of 1.5 * 2^23 rounds it to nearest-even
+                    q[e] = __builtin_bit_cast(uint32_t, __builtin_fmaf(load16_bits<BF16>(ph), 127.0f, 12582912.0f));
+                    q[e + 1] = __builtin_bit_cast(uint32_t, __builtin_fmaf(load16_bits<BF16>(ph >> 16), 127.0f, 12582912.0f));
                 }
                 fp[g] = (int)pack4_low_bytes(q[0], q[1], q[2], q[3]);
             }
@@ -275,10 +290,9 @@ __global__ __launch_bounds__(256, 2) void attn_i8_kernel(const AttnArgs p)
     for (int jn = 0; jn < NB; ++jn)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            uint32_t o[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = dequant_one<BF16>(acc_o[jn][4 * g + e], alpha2, 0.0f, false, false, 0u, false);
-            *(v2u*)(stg + r32 * PITCH + (32 * jn + 8 * g + 4 * h) * 2) = v2u{o[0] | (o[1] << 16), o[2] | (o[3] << 16)};
+            const uint32_t o01 = dequant_pair<BF16>(acc_o[jn][4 * g], acc_o[jn][4 * g + 1], alpha2, alpha2, 0.0f, 0.0f, false, false, 0u, false);
+            const uint32_t o23 = dequant_pair<BF16>(acc_o[jn][4 * g + 2], acc_o[jn][4 * g + 3], alpha2, alpha2, 0.0f, 0.0f, false, false, 0u, false);
+            *(v2u*)(stg + r32 * PITCH + (32 * jn + 8 * g + 4 * h) * 2) = v2u{o01, o23};
         }
     __builtin_amdgcn_wave_barrier();
     uint16_t* Ob = (uint16_t*)p.O + (int64_t)batch * p.stride_o;

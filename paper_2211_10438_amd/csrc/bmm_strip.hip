@@ -154,11 +154,11 @@ __global__ __launch_bounds__(320, WPE) void bmm_strip_kernel(const GemmArgs p, c
             for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    uint32_t o[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        o[e] = dequant_one<BF16>(acc[2 * h + jj][4 * g + e], alpha, 0.0f, false, false, 0u, false);
-                    *(v2u*)(stg + st_w + (jj * 32 + 8 * g) * 2) = v2u{o[0] | (o[1] << 16), o[2] | (o[3] << 16)};
+                    const uint32_t o01 = dequant_pair<BF16>(acc[2 * h + jj][4 * g], acc[2 * h + jj][4 * g + 1], alpha, alpha, 0.0f, 0.0f, false,
+                                                            false, 0u, false);
+                    const uint32_t o23 = dequant_pair<BF16>(acc[2 * h + jj][4 * g + 2], acc[2 * h + jj][4 * g + 3], alpha, alpha, 0.0f, 0.0f,
+                                                            false, false, 0u, false);
+                    *(v2u*)(stg + st_w + (jj * 32 + 8 * g) * 2) = v2u{o01, o23};
                 }
             __builtin_amdgcn_wave_barrier();  // LDS serves one wave's accesses in order; keep the compiler from reordering
 #pragma unroll

@@ -52,6 +52,18 @@ SQ_DEVICE uint32_t dequant_one(int acc, float c, float bias, bool has_bias, bool
     return store16_bits<BF16>(v);
 }
 
+// The same for two neighbouring outputs, narrowed together (lo = first): one conversion instruction for the pair.
+template <bool BF16>
+SQ_DEVICE uint32_t dequant_pair(int acc0, int acc1, float c0, float c1, float bias0, float bias1, bool has_bias, bool relu,
+                                uint32_t res_pair, bool has_res)
+{
+    float v0 = (float)acc0 * c0, v1 = (float)acc1 * c1;
+    if (has_bias) { v0 = v0 + bias0; v1 = v1 + bias1; }
+    if (relu) { v0 = v0 > 0.0f ? v0 : 0.0f; v1 = v1 > 0.0f ? v1 : 0.0f; }
+    if (has_res) { v0 = v0 + load16_bits<BF16>(res_pair); v1 = v1 + load16_bits<BF16>(res_pair >> 16); }
+    return store16x2_bits<BF16>(v0, v1);
+}
+
 // Weight-streaming GEMM for few-token shapes (gemm_i8_stream.hip).  sq_stream_gemm_splits returns 0
 // when the shape is left to the tile kernels, else the number of K splits of its plan: 1 = the kernel
 // writes the final output itself; > 1 = it writes int32 partial sums to a.acc_out[splits][M][N] (which

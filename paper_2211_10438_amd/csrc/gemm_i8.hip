@@ -449,12 +449,11 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
                         v2u* slot = (v2u*)(smem + lrow * PITCH + lcol * 2);
                         v2u rb = {0u, 0u};
                         if constexpr (has_res) rb = *slot;
-                        uint32_t o[4];
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            o[e] = dequant_one<BF16>(acc[i][j][4 * g + e], cq[e], bq[e], has_bias, relu, rb[e >> 1] >> ((e & 1) * 16),
-                                                     has_res);
-                        *slot = v2u{o[0] | (o[1] << 16), o[2] | (o[3] << 16)};
+                        const uint32_t o01 = dequant_pair<BF16>(acc[i][j][4 * g], acc[i][j][4 * g + 1], cq[0], cq[1], bq[0], bq[1], has_bias,
+                                                                relu, rb[0], has_res);
+                        const uint32_t o23 = dequant_pair<BF16>(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3], cq[2], cq[3], bq[2], bq[3],
+                                                                has_bias, relu, rb[1], has_res);
+                        *slot = v2u{o01, o23};
                     }
             }
         };
