@@ -245,19 +245,32 @@ __global__ __launch_bounds__(256, 2) void attn_i8_kernel(const AttnArgs p)
                     fp[g] = 0;
                     continue;
                 }
-                uint32_t q[4];
+                uint32_t ph[2];  // the probabilities of columns e = 0,1 and 2,3 as 16-bit pairs (the softmax output is a 16-bit tensor)
 #pragma unroll
                 for (int e = 0; e < 4; e += 2) {
                     float s0, s1;
                     s16f2(acc[ks][4 * g + e], acc[ks][4 * g + e + 1], s0, s1);
                     const float pr0 = __builtin_amdgcn_exp2f(__builtin_fmaf(s0, kLog2e, nm));
                     const float pr1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s1, kLog2e, nm));
-                    const uint32_t ph = store16x2_bits<BF16>(pr0, pr1);  // the softmax output is a 16-bit tensor
-                    // round(127 p16): the product is exact in fp32, the add of 1.5 * 2^23 rounds it to nearest-even
-                    q[e] = __builtin_bit_cast(uint32_t, __builtin_fmaf(load16_bits<BF16>(ph), 127.0f, 12582912.0f));
-                    q[e + 1] = __builtin_bit_cast(uint32_t, __builtin_fmaf(load16_bits<BF16>(ph >> 16), 127.0f, 12582912.0f));
+                    ph[e >> 1] = store16x2_bits<BF16>(pr0, pr1);
                 }
-                fp[g] = (int)pack4_low_bytes(q[0], q[1], q[2], q[3]);
+                if constexpr (BF16) {
+                    // round(127 p16): the product is exact in fp32, the add of 1.5 * 2^23 rounds it to nearest-even and
+                    // leaves the code in the low mantissa byte
+                    uint32_t q[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        q[e] = __builtin_bit_cast(uint32_t, __builtin_fmaf(load16_bits<true>(ph[e >> 1] >> ((e & 1) * 16)), 127.0f, 12582912.0f));
+                    fp[g] = (int)pack4_low_bytes(q[0], q[1], q[2], q[3]);
+                } else {
+                    // the same in packed fp16, two codes per instruction: fma(p16, 127, 1024) is one rounding of the exact
+                    // 127 p16 + 1024 to a grid of spacing 1 (fp16 in [1024, 2048)), i.e. 1024 + round-half-even(127 p16), the
+                    // code in the low byte of each half; one byte permute gathers the four codes
+                    const sq_f16x2 k127 = {(_Float16)127.0f, (_Float16)127.0f}, k1024 = {(_Float16)1024.0f, (_Float16)1024.0f};
+                    const uint32_t c01 = __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(__builtin_bit_cast(sq_f16x2, ph[0]), k127, k1024));
+                    const uint32_t c23 = __builtin_bit_cast(uint32_t, __builtin_elementwise_fma(__builtin_bit_cast(sq_f16x2, ph[1]), k127, k1024));
+                    fp[g] = (int)__builtin_amdgcn_perm(c23, c01, 0x06040200u);
+                }
             }
             if (Prow) {
 #pragma unroll
