@@ -19,7 +19,7 @@ def _progress(msg):
 
 # ------------------------------------------------------------------ quantize_act
 
-QUANT_SHAPES = [(1, 16), (3, 48), (16, 768), (5, 1040), (7, 2064), (33, 5120), (4, 12288), (2, 49152), (2, 65552),
+QUANT_SHAPES = [(1, 16), (3, 48), (16, 768), (5, 1040), (7, 2064), (33, 5120), (4, 12288), (5, 12288), (3, 9216), (2, 49152), (2, 65552),
                 (260, 128), (9, 3088)]
 
 
