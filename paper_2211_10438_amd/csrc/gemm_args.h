@@ -53,15 +53,22 @@ SQ_DEVICE uint32_t dequant_one(int acc, float c, float bias, bool has_bias, bool
 }
 
 // The same for two neighbouring outputs, narrowed together (lo = first): one conversion instruction for the pair.
+// (the accumulators arrive already converted to fp32: exact up to 2^24, round-to-nearest-even beyond, like the cast)
 template <bool BF16>
-SQ_DEVICE uint32_t dequant_pair(int acc0, int acc1, float c0, float c1, float bias0, float bias1, bool has_bias, bool relu,
-                                uint32_t res_pair, bool has_res)
+SQ_DEVICE uint32_t dequant_pair_f(float acc0, float acc1, float c0, float c1, float bias0, float bias1, bool has_bias, bool relu,
+                                  uint32_t res_pair, bool has_res)
 {
-    float v0 = (float)acc0 * c0, v1 = (float)acc1 * c1;
+    float v0 = acc0 * c0, v1 = acc1 * c1;
     if (has_bias) { v0 = v0 + bias0; v1 = v1 + bias1; }
     if (relu) { v0 = v0 > 0.0f ? v0 : 0.0f; v1 = v1 > 0.0f ? v1 : 0.0f; }
     if (has_res) { v0 = v0 + load16_bits<BF16>(res_pair); v1 = v1 + load16_bits<BF16>(res_pair >> 16); }
     return store16x2_bits<BF16>(v0, v1);
+}
+template <bool BF16>
+SQ_DEVICE uint32_t dequant_pair(int acc0, int acc1, float c0, float c1, float bias0, float bias1, bool has_bias, bool relu,
+                                uint32_t res_pair, bool has_res)
+{
+    return dequant_pair_f<BF16>((float)acc0, (float)acc1, c0, c1, bias0, bias1, has_bias, relu, res_pair, has_res);
 }
 
 // Weight-streaming GEMM for few-token shapes (gemm_i8_stream.hip).  sq_stream_gemm_splits returns 0

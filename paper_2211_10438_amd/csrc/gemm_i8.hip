@@ -389,6 +389,16 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
         const bool vec_ok = (p.N & 7) == 0;  // 16-byte chunks never straddle the row end and stay aligned
         const float ws = (p.x_scale && !p.w_per_channel) ? p.w_scale[0] : 0.0f;
         const float xs0 = (p.x_scale && !p.per_token) ? p.x_scale[0] : 0.0f;
+        // Accumulators to fp32 in place, before anything else of the epilogue: the conversion does not depend on the
+        // row group or on the optional terms, so the compiler moves it in front of the loop and the switch below
+        // anyway, and into new registers if left to itself (the 384-wide tile then spilled thirty per lane).
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                typedef float v16f __attribute__((ext_vector_type(16)));
+                acc[i][j] = __builtin_bit_cast(v16i, __builtin_convertvector(acc[i][j], v16f));
+            }
         float rq = 0.0f;
         if (p.q8_step) {
             const float delta = p.q8_step[0];
@@ -397,6 +407,11 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
 #pragma unroll
         for (int eg = 0; eg < EG; ++eg) {
         const int g0 = eg * GR;  // first tile row of this group
+        // A zero the compiler cannot see through, added to the row and column offsets below: without it every index,
+        // bounds predicate and bias / scale address of all variants of phase1 counts as independent of the row group and
+        // is computed in front of this loop, where some ninety such values stay live next to the accumulators.
+        int opaque0;
+        asm volatile("s_mov_b32 %0, 0" : "=s"(opaque0));
         __syncthreads();  // operand reads (first group) or the previous group's stores out of LDS are done
         if (R) {
             for (int q = threadIdx.x; q < GR * CPR; q += NW * 64) {
@@ -425,7 +440,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
 #pragma unroll
             for (int i = 0; i < MI; ++i) {
                 if (EG > 1 && (wm * WM + i * 32) / GR != eg) continue;  // rows of another group
-                const int lrow = wm * WM + i * 32 + row_l - g0;
+                const int lrow = wm * WM + i * 32 + row_l - g0 + opaque0;
                 const int row = m0 + g0 + lrow;
                 const float xrow = p.x_scale ? (p.per_token ? p.x_scale[row < p.M ? row : p.M - 1] : xs0) : 0.0f;
                 float c;
@@ -435,7 +450,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
                 for (int j = 0; j < NI; ++j)
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
-                        const int lcol = wn * WN + j * 32 + 8 * g + col_l;
+                        const int lcol = wn * WN + j * 32 + 8 * g + col_l + opaque0;
                         float cq[4] = {c, c, c, c};
                         if (p.w_per_channel) {  // c = Delta_X[row] * Delta_W[col]
 #pragma unroll
@@ -449,10 +464,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
                         v2u* slot = (v2u*)(smem + lrow * PITCH + lcol * 2);
                         v2u rb = {0u, 0u};
                         if constexpr (has_res) rb = *slot;
-                        const uint32_t o01 = dequant_pair<BF16>(acc[i][j][4 * g], acc[i][j][4 * g + 1], cq[0], cq[1], bq[0], bq[1], has_bias,
-                                                                relu, rb[0], has_res);
-                        const uint32_t o23 = dequant_pair<BF16>(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3], cq[2], cq[3], bq[2], bq[3],
-                                                                has_bias, relu, rb[1], has_res);
+                        auto fa = [&](int e) {
+                            const int bits = acc[i][j][4 * g + e];  // a copy: a vector element is no object to cast from
+                            return __builtin_bit_cast(float, bits);
+                        };
+                        const uint32_t o01 = dequant_pair_f<BF16>(fa(0), fa(1), cq[0], cq[1], bq[0], bq[1], has_bias, relu, rb[0], has_res);
+                        const uint32_t o23 = dequant_pair_f<BF16>(fa(2), fa(3), cq[2], cq[3], bq[2], bq[3], has_bias, relu, rb[1], has_res);
                         *slot = v2u{o01, o23};
                     }
             }
