@@ -603,16 +603,17 @@ Plan make_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split,
         const int64_t rounds192 = (tm * ((N + 191) / 192) * batch + kNumCU - 1) / kNumCU;
         const bool use192 = rounds192 * 224 < rounds256 * 256;
         if (use192) { pl.cfg = 6; pl.bn = 192; }
-        // 256x384 tiles (192 accumulator registers per lane, the whole 160 KB of LDS, epilogue in two halves):
-        // 4 % fewer cycles per multiply-accumulate in the K loop but a longer fill and epilogue.  Measured per tile,
-        // in microseconds: K steps x 0.59 + 6 (192 wide), x 0.70 + 18 (256), x 1.005 + 31 (384).  Taken where
-        // that model promises at least 4 % (it pays when the wider tile saves a round of tiles: 2048 tokens into
-        // 36864 or 12288 channels, not into 49152).
+        // 256x384 tiles (192 accumulator registers per lane, the whole 160 KB of LDS, epilogue in two halves): fewer
+        // operand bytes per multiply-accumulate and fewer rounds of tiles.  Measured per tile on quantized Gaussian
+        // operands (the clock the power cap allows is part of these figures), in microseconds: K steps x 0.59 + 6
+        // (192 wide), x 0.70 + 18 (256), x 1.12 + 8 (384).  Taken where that model promises at least 2 %: with 2048
+        // tokens all four OPT-175B layers (3 rounds instead of 5, 1 instead of 2, 4 instead of 6), with 4096 tokens
+        // of OPT-66B only FC1.
         const int64_t rounds384 = (tm * ((N + 383) / 384) * batch + kNumCU - 1) / kNumCU;
         const double nks = (double)((K + 63) / 64);
         const double t_now = use192 ? rounds192 * (nks * 0.588 + 6.0) : rounds256 * (nks * 0.70 + 18.0);
-        const double t384 = rounds384 * (nks * 1.005 + 31.0);
-        if (t384 < 0.96 * t_now) { pl.cfg = 9; pl.bn = 384; }
+        const double t384 = rounds384 * (nks * 1.12 + 8.0);
+        if (t384 < 0.98 * t_now) { pl.cfg = 9; pl.bn = 384; }
     }
     else if (M > 64) { pl.cfg = 1; pl.bm = 128; }
     else if (M > 32) { pl.cfg = 2; pl.bm = 64; }
