@@ -75,7 +75,7 @@ SQ_DEVICE uint32_t dequant_pair(int acc0, int acc1, float c0, float c1, float bi
 // when the shape is left to the tile kernels, else the number of K splits of its plan: 1 = the kernel
 // writes the final output itself; > 1 = it writes int32 partial sums to a.acc_out[splits][M][N] (which
 // the caller points at a workspace) and the split-K reduction kernel finishes the job.
-int sq_stream_gemm_splits(int64_t M, int64_t N, int64_t K, int64_t batch);
+int sq_stream_gemm_splits(int64_t M, int64_t N, int64_t K, int64_t batch, bool tiled);
 void sq_stream_gemm_launch(const GemmArgs& a, bool to_i32, bool bf16, bool tiled, hipStream_t st);
 
 // Strip kernel for attention scores (bmm_strip.hip): B = [N, K] with K <= 128, alpha-only epilogue.

@@ -697,7 +697,7 @@ sq_status run_gemm(GemmArgs a, int64_t batch, bool to_i32, bool bf16, void* work
         if (bf16) sq_launch(splitk_reduce_kernel<true>, dim3(blocks), dim3(256), 0, st, a, to_i32 ? 1 : 0);
         else sq_launch(splitk_reduce_kernel<false>, dim3(blocks), dim3(256), 0, st, a, to_i32 ? 1 : 0);
     };
-    int ss = b_transposed ? 0 : sq_stream_gemm_splits(a.M, a.N, a.K, batch);
+    int ss = b_transposed ? 0 : sq_stream_gemm_splits(a.M, a.N, a.K, batch, tiled);
     if (ss > 1 && !allow_split) ss = 0;  // the streaming plan wants a K split: leave the shape to the tile kernels
     if (ss) {
         // few tokens, wide C_o: stream W once through one workgroup per CU
@@ -750,7 +750,9 @@ extern "C" {
 size_t sq_gemm_workspace_bytes(int64_t t, int64_t c_i, int64_t c_o)
 {
     if (!dims_ok(t, c_i, c_o)) return 0;
-    if (const int ss = sq_stream_gemm_splits(t, c_o, c_i, 1)) return ss > 1 ? (size_t)ss * t * c_o * sizeof(int32_t) : 0;
+    // the layout is not known here: enough for the plan of either
+    const int ss_rows = sq_stream_gemm_splits(t, c_o, c_i, 1, false), ss_tiled = sq_stream_gemm_splits(t, c_o, c_i, 1, true);
+    if (const int ss = ss_rows > ss_tiled ? ss_rows : ss_tiled) return ss > 1 ? (size_t)ss * t * c_o * sizeof(int32_t) : 0;
     Plan pl = make_plan(t, c_o, c_i, 1, true);
     return pl.splits > 1 ? (size_t)pl.splits * t * c_o * sizeof(int32_t) : 0;
 }

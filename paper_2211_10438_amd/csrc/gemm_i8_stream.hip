@@ -36,6 +36,7 @@ struct StreamArgs {
     int ksub;        // 64-byte K steps per stage
     int iters;       // stages per workgroup: K / 64 / gk / ksub
     int nt_w;        // weight loads carry the non-temporal hint
+    int regs;        // the register-direct kernel (tiled operands) runs this plan
     int tiled, to_i32, bf16;
 };
 
@@ -224,6 +225,216 @@ __global__ __launch_bounds__(NWAVE * 64, 1) void gemm_i8_stream_kernel(const Gem
     }
 }
 
+// ---- Variant for tiled operands: weights straight into registers, activations through two loader waves.
+// Two measurements with pure read loops (256 workgroups, 4 streaming waves each) shape it:
+//  * a wave's loads return in issue order, so an activation block that would be an L2 hit waits behind the HBM
+//    misses the same wave issued before it.  A QKV-sized weight stream (453 MB) takes 65 us alone; with every wave
+//    also reading its share of a 1.5 MB block common to all workgroups (128 tokens) 108 us; with the common block read
+//    by two extra waves of each workgroup instead 75 us;
+//  * more requests in flight than the latency needs cost bandwidth: 9 interleaved 1 KB streams per wave deliver
+//    6.9 TB/s with 9 loads in flight per wave, 5.8 with 18, 5.3 with 27, 4.8 with 45.
+// In the tiled layout a 1 KB block is one MFMA operand as it lies in memory, so the four compute waves fetch their
+// weight blocks with one 16-byte load per lane straight into registers (no LDS, no barrier, no other wave to wait for),
+// D K steps deep, 8-24 loads in flight.  Wave w owns the units w, w + 4, ... of the slab over the whole K range of the
+// workgroup.  Waves 4 and 5 do nothing but copy the activation blocks into a 4-stage LDS ring (global_load_lds, a
+// stage = 4 K steps of all token blocks), three stages ahead; one barrier per stage.  Used from 33 tokens on; below,
+// where the activation bytes hardly matter, the kernel above is faster (all eight waves' loads feed one ring).
+// Tried on top of this and measured slower: the 32x32x32 MFMA (v_mfma_i32_16x16x64_i8 issues at half the rate per
+// multiply-accumulate: 32-48 against 34-37 cycles for half the work) on operands loaded half a block per instruction
+// (twice the cache lines per load: a third slower) or formed from whole blocks of two units with v_permlane16_swap
+// (25 % slower); K slices instead of units per wave with both operands straight into registers (the activation blocks
+// then wait behind the weight blocks again).
+constexpr int kRegsStageSteps = 4, kRegsStages = 4;
+constexpr int regs_depth(int cntw) { return cntw <= 3 ? 8 : 4; }  // K steps of weight blocks in flight per wave
+
+template <int MB, int CNT, bool NT>
+__global__ __launch_bounds__(384, 1) void gemm_i8_stream_regs_kernel(const GemmArgs p, const StreamArgs q)
+{
+    constexpr int CNTW = (CNT + 3) / 4;       // units per compute wave
+    constexpr int D = regs_depth(CNTW);
+    constexpr int S = kRegsStageSteps, NS = kRegsStages;
+    constexpr int STAGE = S * MB * 1024;      // bytes
+    constexpr int LW = S * MB / 2;            // loads per loader wave and stage
+    constexpr int PITCH = CNT * 16 + 4;       // ints per row of the output staging buffer
+    constexpr int RING = NS * STAGE, RED = MB * 16 * PITCH * 4;
+    __shared__ __attribute__((aligned(1024))) char smem[RING > RED ? RING : RED];
+    static_assert(S * MB % 2 == 0 && 3 * LW <= 63, "loads of a loader wave: whole, and countable by vmcnt");
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int gs = blockIdx.x % q.gn, gki = blockIdx.x / q.gn;
+    const int u0 = (int)((int64_t)gs * q.units / q.gn), u1 = (int)((int64_t)(gs + 1) * q.units / q.gn);
+    const int nu = u1 - u0;     // 1 <= nu <= CNT; units past the slab re-read its last one and their sums are dropped
+    const int n = q.iters;      // 64-byte K steps of this workgroup: at least D (the host sees to it)
+    const int nst = (n + S - 1) / S;  // stages
+    const int64_t k0 = (int64_t)gki * n * 1024;
+
+    // lane l feeds row (l & 15), K chunk (l >> 4) of a block; the chunks of a row are stored permuted
+    const int frow = lane & 15;
+    const uint32_t frag_off = (uint32_t)(frow * 64 + ((((lane >> 4) ^ ((frow >> 1) & 3) ^ ((frow >> 3) & 1))) << 4));
+
+    v4i acc[MB][CNTW];
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < CNTW; ++j) acc[i][j] = v4i{0, 0, 0, 0};
+
+    if (wave >= 4) {
+        // ---- loader waves: block b of a stage = (K step b / MB of the stage, token block b % MB); wave 4 takes the
+        // even blocks, wave 5 the odd ones.  Ragged M: blocks past the last one re-read it (their rows are never stored).
+        const int lw = wave - 4;
+        const int last_a = (p.M - 1) >> 4;
+        const int8_t* src[LW];
+        int step_of[LW];
+#pragma unroll
+        for (int i = 0; i < LW; ++i) {
+            const int b = 2 * i + lw;
+            const int blk = b % MB;
+            step_of[i] = b / MB;
+            src[i] = p.A + (int64_t)(blk < last_a ? blk : last_a) * 16 * p.lda + k0 + lane * 16;
+        }
+        auto issue_stage = [&](int t, int slot) {
+            char* base = smem + slot * STAGE + lw * 1024;
+#pragma unroll
+            for (int i = 0; i < LW; ++i) {
+                int s = t * S + step_of[i];
+                s = s < n ? s : n - 1;  // past the end of the K range: the last step again, nobody reads it
+                __builtin_amdgcn_global_load_lds(GPTR(src[i] + (int64_t)s * 1024), LPTR(base + i * 2048), 16, 0, 0);
+            }
+        };
+        // Every iteration issues exactly one stage of loads (past the end the last stage again, into a slot nobody
+        // reads), so the wait is one immediate: stage t has landed when at most two younger stages are in flight.
+#pragma unroll
+        for (int t = 0; t < NS - 1; ++t) issue_stage(t < nst ? t : nst - 1, t);
+        int slot = 0;
+        for (int t = 0; t < nst; ++t) {
+            wait_vmcnt_imm<2 * LW>();
+            __builtin_amdgcn_s_barrier();  // stage t is there for everyone; everyone is done with stage t - 1
+            const int nxt = t + NS - 1;
+            issue_stage(nxt < nst ? nxt : nst - 1, slot == 0 ? NS - 1 : slot - 1);
+            slot = slot + 1 == NS ? 0 : slot + 1;
+        }
+        wait_vmcnt_imm<0>();
+    } else {
+        // ---- compute waves
+        const int8_t* pw[CNTW];
+#pragma unroll
+        for (int j = 0; j < CNTW; ++j) {
+            const int u = wave + j * 4;
+            pw[j] = p.B + (int64_t)(u0 + (u < nu ? u : nu - 1)) * 16 * p.ldb + k0;
+        }
+        v4i fb[D][CNTW];
+        auto load_w = [&](int d, int j, int s) {
+            const uint32_t off = frag_off + (uint32_t)s * 1024u;
+            if (NT) fb[d][j] = __builtin_nontemporal_load((const v4i*)(pw[j] + off));
+            else fb[d][j] = *(const v4i*)(pw[j] + off);
+        };
+        // Every step issues its refills, past the end of the range the last step again (L2 hits whose data nobody
+        // uses): the number of loads issued after any given one is then the same on every path, and the waits the
+        // compiler places leave exactly the younger loads in flight.  (With a refill under a condition it has to
+        // assume the refill did not happen, and waits for everything.)
+#pragma unroll
+        for (int d = 0; d < D; ++d)
+#pragma unroll
+            for (int j = 0; j < CNTW; ++j) load_w(d, j, d);
+        static_assert(D % S == 0, "stage boundaries at fixed places of the unrolled body");
+        int slot = 0;
+        for (int k = 0; k < nst * S; k += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                if (d % S == 0) {
+                    if (k + d >= nst * S) break;  // D = 8: the second stage of the last round may not exist
+                    __builtin_amdgcn_s_barrier();
+                }
+                const bool live = k + d < n;
+                const int sw = k + d + D < n ? k + d + D : n - 1;
+                const char* sa = smem + slot * STAGE + (d % S) * MB * 1024 + frag_off;
+                v4i fa[MB];
+#pragma unroll
+                for (int i = 0; i < MB; ++i) fa[i] = *(const v4i*)(sa + i * 1024);
+#pragma unroll
+                for (int j = 0; j < CNTW; ++j) {
+                    if (live) {
+#pragma unroll
+                        for (int i = 0; i < MB; ++i)
+                            acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fa[i], fb[d][j], acc[i][j], 0, 0, 0);
+                    }
+                    load_w(d, j, sw);
+                }
+                if (d % S == S - 1) slot = slot + 1 == NS ? 0 : slot + 1;
+            }
+        }
+    }
+
+    // ---- the accumulators go through LDS (the ring is free now) so that the epilogue writes whole rows of the slab.
+    // 16x16 accumulator layout: lane l, register v holds row 4*(l >> 4) + v, column l & 15.
+    int* red = (int*)smem;
+    __syncthreads();  // everyone is done with the ring
+    if (wave < 4) {
+        const int col_l = lane & 15, row_l = (lane >> 4) * 4;
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+            for (int j = 0; j < CNTW; ++j) {
+                const int u = wave + j * 4;
+                if (u >= nu) continue;  // a re-read unit
+#pragma unroll
+                for (int v = 0; v < 4; ++v) red[(i * 16 + row_l + v) * PITCH + u * 16 + col_l] = acc[i][j][v];
+            }
+    }
+    __syncthreads();
+
+    // ---- epilogue: two neighbouring columns per thread
+    const bool raw = q.to_i32 || q.gk > 1;
+    int32_t* out32 = p.acc_out + (int64_t)gki * p.M * p.N;
+    const float ws = (!raw && p.x_scale && !p.w_per_channel) ? p.w_scale[0] : 0.0f;
+    const uint16_t* R = (const uint16_t*)p.residual;
+    float rq = 0.0f;
+    if (!raw && p.q8_step) {
+        const float delta = p.q8_step[0];
+        rq = delta > 0.0f ? 1.0f / delta : 0.0f;
+    }
+    const int pairs = nu * 8;  // column pairs per row
+    const int rows = p.M < MB * 16 ? p.M : MB * 16;
+    for (int idx = threadIdx.x; idx < rows * pairs; idx += 384) {
+        const int row = idx / pairs, cp = idx - row * pairs;
+        const int col = u0 * 16 + cp * 2;
+        if (col >= p.N) continue;
+        const bool two = col + 1 < p.N;
+        const int a0 = red[row * PITCH + cp * 2], a1 = red[row * PITCH + cp * 2 + 1];
+        const int64_t o = (int64_t)row * p.N + col;
+        if (raw) {
+            out32[o] = a0;
+            if (two) out32[o + 1] = a1;
+            continue;
+        }
+        const float xs = p.x_scale ? (p.per_token ? p.x_scale[row] : p.x_scale[0]) : 0.0f;
+        uint32_t ob[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            if (e == 1 && !two) break;
+            const float c = p.x_scale ? xs * (p.w_per_channel ? p.w_scale[col + e] : ws) : p.alpha;
+            const float bias = p.bias ? p.bias[col + e] : 0.0f;
+            const uint32_t rb = R ? (uint32_t)R[o + e] : 0u;
+            const int a = e ? a1 : a0;
+            ob[e] = q.bf16 ? dequant_one<true>(a, c, bias, p.bias != nullptr, p.relu != 0, rb, R != nullptr)
+                           : dequant_one<false>(a, c, bias, p.bias != nullptr, p.relu != 0, rb, R != nullptr);
+            if (p.q8_step) {
+                const int code = q.bf16 ? requant_code<true>(ob[e], rq) : requant_code<false>(ob[e], rq);
+                code_dst(p.q8_out, row, (col + e) & ~7, p.N, p.q8_tiled != 0)[(col + e) & 7] = (int8_t)code;
+            }
+        }
+        if (p.q8_step) continue;
+        uint16_t* dst = (uint16_t*)p.C + o;
+        if (two && !(p.N & 1)) {
+            *(uint32_t*)dst = (ob[0] & 0xffffu) | (ob[1] << 16);
+        } else {
+            dst[0] = (uint16_t)ob[0];
+            if (two) dst[1] = (uint16_t)ob[1];
+        }
+    }
+}
+
 int num_cus()
 {
     static int n = 0;
@@ -243,7 +454,7 @@ int num_cus()
 //             at about 26 GB/s while most loads miss to HBM; workgroups beyond one per CU run in rounds;
 //   HBM side: W once plus the int32 partials when K is split, at about 5.5 TB/s;
 //   a K split adds the reduction kernel (launch + reading the partials).
-bool make_stream_plan(int64_t M, int64_t N, int64_t K, int64_t batch, StreamArgs* out)
+bool make_stream_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool tiled, StreamArgs* out)
 {
     if (batch != 1 || M < 1 || M > 128 || (K & 63) || K < 64) return false;
     const int64_t units = (N + 15) / 16;
@@ -251,8 +462,11 @@ bool make_stream_plan(int64_t M, int64_t N, int64_t K, int64_t batch, StreamArgs
     if (units < cus) return false;  // narrow C_o: the tile kernels with split-K cover it
     const int na = M <= 16 ? 1 : M <= 32 ? 2 : M <= 64 ? 4 : 8;
     const int nk = (int)(K >> 6);
-    const double cu_rate = 26e9, hbm_rate = 5.5e12, red_rate = 4e12, red_launch = 5e-6;
-    const int s_max = na == 8 ? 24 : 16;  // widest slab the kernel shapes accumulate
+    // Tiled operands with more than 32 tokens go to the kernel with loader waves: a CU moves a little more per second
+    // there (fitted to the OPT-175B layers at 64 and 128 tokens), and a wave accumulates up to 4 of at most 16 units.
+    const bool regs = tiled && na >= 4;
+    const double cu_rate = regs ? 32e9 : 26e9, hbm_rate = regs ? 6.0e12 : 5.5e12, red_rate = 4e12, red_launch = 5e-6;
+    const int s_max = regs ? 16 : (na == 8 ? 24 : 16);  // widest slab the kernel shapes accumulate
     double best = 1e30, best_cu = 1e30;
     int best_gn = 0, best_gk = 0;
     for (int gk = 1; gk <= 8; ++gk) {
@@ -286,34 +500,53 @@ bool make_stream_plan(int64_t M, int64_t N, int64_t K, int64_t batch, StreamArgs
     const int nblk = na + (int)((units + best_gn - 1) / best_gn);
     const int nks = nk / best_gk;
     q.ksub = 1;
-    for (int c = 4; c > 1; c >>= 1)
-        if (nblk * c <= max_stage_blocks(na >= 4 ? 8 : 4) && nks % c == 0) { q.ksub = c; break; }
+    q.regs = regs ? 1 : 0;
+    if (regs) {
+        // a compute wave starts with 8 K steps of weight blocks; shorter ranges go to the LDS-ring kernel
+        if (nks < 8) return make_stream_plan(M, N, K, batch, false, out);
+    }
+    if (!regs)
+        for (int c = 4; c > 1; c >>= 1)
+            if (nblk * c <= max_stage_blocks(na >= 4 ? 8 : 4) && nks % c == 0) { q.ksub = c; break; }
     q.iters = nks / q.ksub;
     // W is read exactly once: the non-temporal hint keeps it from displacing the activation block in the caches.
     // Measured: +7..12 % at up to 16 tokens; with more tokens it pays only for wide slabs (at least 10 units and
     // three times as many units as activation blocks) and costs a few percent otherwise.
     const int smax = nblk - na;
-    q.nt_w = (na == 1 || (smax >= 3 * na && smax >= 10)) ? 1 : 0;
+    q.nt_w = (regs || na == 1 || (smax >= 3 * na && smax >= 10)) ? 1 : 0;
     if (out) *out = q;
     return true;
 }
 
 }  // namespace
 
-int sq_stream_gemm_splits(int64_t M, int64_t N, int64_t K, int64_t batch)
+int sq_stream_gemm_splits(int64_t M, int64_t N, int64_t K, int64_t batch, bool tiled)
 {
     StreamArgs q{};
-    return make_stream_plan(M, N, K, batch, &q) ? q.gk : 0;
+    return make_stream_plan(M, N, K, batch, tiled, &q) ? q.gk : 0;
 }
 
 void sq_stream_gemm_launch(const GemmArgs& a, bool to_i32, bool bf16, bool tiled, hipStream_t st)
 {
     StreamArgs q{};
-    if (!make_stream_plan(a.M, a.N, a.K, 1, &q)) return;
+    if (!make_stream_plan(a.M, a.N, a.K, 1, tiled, &q)) return;
     q.tiled = tiled ? 1 : 0;
     q.to_i32 = to_i32 ? 1 : 0;
     q.bf16 = bf16 ? 1 : 0;
     const dim3 grid((unsigned)(q.gn * q.gk)), block(256), block8(512);
+    if (q.regs) {
+        const int cnt = (q.units + q.gn - 1) / q.gn;  // widest slab
+#define SQ_R(MB, C) case C: sq_launch((gemm_i8_stream_regs_kernel<MB, C, true>), grid, dim3(384), 0, st, a, q); break;
+#define SQ_R16(MB) SQ_R(MB, 1) SQ_R(MB, 2) SQ_R(MB, 3) SQ_R(MB, 4) SQ_R(MB, 5) SQ_R(MB, 6) SQ_R(MB, 7) SQ_R(MB, 8) \
+                   SQ_R(MB, 9) SQ_R(MB, 10) SQ_R(MB, 11) SQ_R(MB, 12) SQ_R(MB, 13) SQ_R(MB, 14) SQ_R(MB, 15) SQ_R(MB, 16)
+        switch (q.na) {
+            case 4: switch (cnt) { SQ_R16(4) default: break; } break;
+            default: switch (cnt) { SQ_R16(8) default: break; } break;
+        }
+#undef SQ_R16
+#undef SQ_R
+        return;
+    }
     switch (q.na * 2 + q.nt_w) {
         case 2: sq_launch((gemm_i8_stream_kernel<1, 1, 4, 4, false>), grid, block, 0, st, a, q); break;
         case 3: sq_launch((gemm_i8_stream_kernel<1, 1, 4, 4, true>), grid, block, 0, st, a, q); break;

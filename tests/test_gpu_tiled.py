@@ -44,7 +44,12 @@ def test_prepare_weight_tiled(c_i, c_o, with_s):
 
 TILED_GEMM = [(1, 64, 16), (16, 768, 3072), (31, 320, 100), (33, 1024, 260), (64, 2048, 256), (100, 1088, 777),
               (129, 320, 515), (256, 512, 256), (257, 1088, 258), (300, 1984, 1000), (512, 5120, 1280), (16, 12288, 1536),
-              (1, 49152, 768), (520, 192, 2064)]
+              (1, 49152, 768), (520, 192, 2064),
+              # weight streaming with more than 32 tokens (loader waves + weights through registers): the shortest K
+              # range it takes and one below it, ragged tokens, slabs of unequal width, K steps that fill neither a
+              # stage nor the unrolled body, a K split, the widest slabs
+              (33, 512, 4096), (40, 448, 4096), (100, 1088, 4112), (128, 4160, 8208), (65, 12288, 4096), (64, 2048, 36880),
+              (128, 1024, 65536)]
 
 
 @pytest.mark.parametrize("t,c_i,c_o", TILED_GEMM)
@@ -61,7 +66,8 @@ def test_i8_gemm_i32_tiled(t, c_i, c_o):
 @pytest.mark.parametrize("t,c_i,c_o,odt,use_bias,relu,use_res", [
     (16, 768, 3072, F16, False, False, False), (70, 1088, 520, BF16, True, False, True),
     (300, 1024, 1000, BF16, False, True, False), (513, 320, 2056, F16, True, True, True),
-    (128, 4096, 768, BF16, True, False, False), (2048, 256, 1536, BF16, False, False, False)])
+    (128, 4096, 768, BF16, True, False, False), (2048, 256, 1536, BF16, False, False, False),
+    (100, 1088, 4104, BF16, True, True, True), (128, 2048, 8192, F16, True, False, True), (48, 12288, 4096, BF16, False, False, False)])
 def test_linear_tiled_end_to_end(t, c_i, c_o, odt, use_bias, relu, use_res):
     """quantize_act (tiled out) -> w8a8_linear (tiled in) with weights prepared tiled, all on the GPU."""
     _progress(f"linear tiled t={t} c_i={c_i} c_o={c_o} out={odt}")
