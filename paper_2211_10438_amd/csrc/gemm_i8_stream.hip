@@ -233,24 +233,27 @@ __global__ __launch_bounds__(NWAVE * 64, 1) void gemm_i8_stream_kernel(const Gem
 //    by two extra waves of each workgroup instead 75 us;
 //  * more requests in flight than the latency needs cost bandwidth: 9 interleaved 1 KB streams per wave deliver
 //    6.9 TB/s with 9 loads in flight per wave, 5.8 with 18, 5.3 with 27, 4.8 with 45.
-// In the tiled layout a 1 KB block is one MFMA operand as it lies in memory, so the four compute waves fetch their
-// weight blocks with one 16-byte load per lane straight into registers (no LDS, no barrier, no other wave to wait for),
-// D K steps deep, 8-24 loads in flight.  Wave w owns the units w, w + 4, ... of the slab over the whole K range of the
-// workgroup.  Waves 4 and 5 do nothing but copy the activation blocks into a 4-stage LDS ring (global_load_lds, a
-// stage = 4 K steps of all token blocks), three stages ahead; one barrier per stage.  Used from 33 tokens on; below,
-// where the activation bytes hardly matter, the kernel above is faster (all eight waves' loads feed one ring).
-// Tried on top of this and measured slower: the 32x32x32 MFMA (v_mfma_i32_16x16x64_i8 issues at half the rate per
-// multiply-accumulate: 32-48 against 34-37 cycles for half the work) on operands loaded half a block per instruction
-// (twice the cache lines per load: a third slower) or formed from whole blocks of two units with v_permlane16_swap
-// (25 % slower); K slices instead of units per wave with both operands straight into registers (the activation blocks
-// then wait behind the weight blocks again).
-constexpr int kRegsStageSteps = 4, kRegsStages = 4;
-constexpr int regs_depth(int cntw) { return cntw <= 3 ? 8 : 4; }  // K steps of weight blocks in flight per wave
+//  * v_mfma_i32_16x16x64_i8 issues every 48 cycles from one wave per SIMD and every 32 from two (the 32x32x32 shape
+//    does twice the work in 34-37): with 128 tokens a single compute wave per SIMD is bound by its MFMAs.
+// In the tiled layout a 1 KB block is one MFMA operand as it lies in memory, so the compute waves fetch their weight
+// blocks with one 16-byte load per lane straight into registers (no LDS, no barrier, no other wave to wait for), D of
+// their K steps deep, about a dozen loads in flight.  Six compute waves = 3 unit groups x 2 K parities: wave (ug, kp)
+// owns the units ug, ug + 3, ... of the slab on the K steps 2 t + kp, so two compute waves share a SIMD, every weight
+// block is fetched by exactly one wave and every activation fragment is read from LDS by three.  Waves 6 and 7 do
+// nothing but copy the activation blocks into a 4-stage LDS ring (global_load_lds, a stage = 4 K steps of all token
+// blocks), three stages ahead; one barrier per stage.  Used from 33 tokens on; below, where the activation bytes hardly
+// matter, the kernel above is faster (all eight waves' loads feed one ring).
+// Tried on top of this, no gain: the 32x32x32 MFMA on operands loaded half a block per instruction (twice the cache
+// lines per load: a third slower) or formed from whole blocks of two units with v_permlane16_swap (same time: the
+// MFMAs are not what the waves wait for); four compute waves, one per SIMD (3-8 % slower); K slices instead of units
+// per wave with both operands straight into registers (the activation blocks then wait behind the weight blocks again).
+constexpr int kRegsStageSteps = 4, kRegsStages = 4, kRegsMaxUnits = 12;
+constexpr int regs_depth(int cntw) { return cntw <= 1 ? 8 : 4; }  // own K steps of weight blocks in flight per wave
 
 template <int MB, int CNT, bool NT>
-__global__ __launch_bounds__(384, 1) void gemm_i8_stream_regs_kernel(const GemmArgs p, const StreamArgs q)
+__global__ __launch_bounds__(512, 1) void gemm_i8_stream_regs_kernel(const GemmArgs p, const StreamArgs q)
 {
-    constexpr int CNTW = (CNT + 3) / 4;       // units per compute wave
+    constexpr int CNTW = (CNT + 2) / 3;       // units per compute wave
     constexpr int D = regs_depth(CNTW);
     constexpr int S = kRegsStageSteps, NS = kRegsStages;
     constexpr int STAGE = S * MB * 1024;      // bytes
@@ -258,6 +261,7 @@ __global__ __launch_bounds__(384, 1) void gemm_i8_stream_regs_kernel(const GemmA
     constexpr int PITCH = CNT * 16 + 4;       // ints per row of the output staging buffer
     constexpr int RING = NS * STAGE, RED = MB * 16 * PITCH * 4;
     __shared__ __attribute__((aligned(1024))) char smem[RING > RED ? RING : RED];
+    static_assert(S == 4 && D % 2 == 0, "a stage is two own steps of a compute wave; whole stages in the unrolled body");
     static_assert(S * MB % 2 == 0 && 3 * LW <= 63, "loads of a loader wave: whole, and countable by vmcnt");
 
     const int lane = threadIdx.x & 63;
@@ -265,13 +269,13 @@ __global__ __launch_bounds__(384, 1) void gemm_i8_stream_regs_kernel(const GemmA
     const int gs = blockIdx.x % q.gn, gki = blockIdx.x / q.gn;
     const int u0 = (int)((int64_t)gs * q.units / q.gn), u1 = (int)((int64_t)(gs + 1) * q.units / q.gn);
     const int nu = u1 - u0;     // 1 <= nu <= CNT; units past the slab re-read its last one and their sums are dropped
-    const int n = q.iters;      // 64-byte K steps of this workgroup: at least D (the host sees to it)
+    const int n = q.iters;      // 64-byte K steps of this workgroup: at least 2 D (the host sees to it)
     const int nst = (n + S - 1) / S;  // stages
     const int64_t k0 = (int64_t)gki * n * 1024;
-
     // lane l feeds row (l & 15), K chunk (l >> 4) of a block; the chunks of a row are stored permuted
     const int frow = lane & 15;
     const uint32_t frag_off = (uint32_t)(frow * 64 + ((((lane >> 4) ^ ((frow >> 1) & 3) ^ ((frow >> 3) & 1))) << 4));
+    const int ug = wave % 3, kp = wave / 3;  // compute waves 0..5
 
     v4i acc[MB][CNTW];
 #pragma unroll
@@ -279,10 +283,10 @@ __global__ __launch_bounds__(384, 1) void gemm_i8_stream_regs_kernel(const GemmA
 #pragma unroll
         for (int j = 0; j < CNTW; ++j) acc[i][j] = v4i{0, 0, 0, 0};
 
-    if (wave >= 4) {
-        // ---- loader waves: block b of a stage = (K step b / MB of the stage, token block b % MB); wave 4 takes the
-        // even blocks, wave 5 the odd ones.  Ragged M: blocks past the last one re-read it (their rows are never stored).
-        const int lw = wave - 4;
+    if (wave >= 6) {
+        // ---- loader waves: block b of a stage = (K step b / MB of the stage, token block b % MB); wave 6 takes the
+        // even blocks, wave 7 the odd ones.  Ragged M: blocks past the last one re-read it (their rows are never stored).
+        const int lw = wave - 6;
         const int last_a = (p.M - 1) >> 4;
         const int8_t* src[LW];
         int step_of[LW];
@@ -316,11 +320,11 @@ __global__ __launch_bounds__(384, 1) void gemm_i8_stream_regs_kernel(const GemmA
         }
         wait_vmcnt_imm<0>();
     } else {
-        // ---- compute waves
+        // ---- compute waves: own step t is K step 2 t + kp, in stage t / 2
         const int8_t* pw[CNTW];
 #pragma unroll
         for (int j = 0; j < CNTW; ++j) {
-            const int u = wave + j * 4;
+            const int u = ug + j * 3;
             pw[j] = p.B + (int64_t)(u0 + (u < nu ? u : nu - 1)) * 16 * p.ldb + k0;
         }
         v4i fb[D][CNTW];
@@ -336,19 +340,20 @@ __global__ __launch_bounds__(384, 1) void gemm_i8_stream_regs_kernel(const GemmA
 #pragma unroll
         for (int d = 0; d < D; ++d)
 #pragma unroll
-            for (int j = 0; j < CNTW; ++j) load_w(d, j, d);
-        static_assert(D % S == 0, "stage boundaries at fixed places of the unrolled body");
+            for (int j = 0; j < CNTW; ++j) load_w(d, j, 2 * d + kp);
         int slot = 0;
-        for (int k = 0; k < nst * S; k += D) {
+        for (int t0 = 0; t0 < 2 * nst; t0 += D) {
 #pragma unroll
             for (int d = 0; d < D; ++d) {
-                if (d % S == 0) {
-                    if (k + d >= nst * S) break;  // D = 8: the second stage of the last round may not exist
+                if (d % 2 == 0) {
+                    if (t0 + d >= 2 * nst) break;  // the later stages of the last round may not exist
                     __builtin_amdgcn_s_barrier();
                 }
-                const bool live = k + d < n;
-                const int sw = k + d + D < n ? k + d + D : n - 1;
-                const char* sa = smem + slot * STAGE + (d % S) * MB * 1024 + frag_off;
+                const int g = 2 * (t0 + d) + kp;
+                const bool live = g < n;
+                const int gw = g + 2 * D;
+                const int sw = gw < n ? gw : n - 1;
+                const char* sa = smem + slot * STAGE + (2 * (d % 2) + kp) * MB * 1024 + frag_off;
                 v4i fa[MB];
 #pragma unroll
                 for (int i = 0; i < MB; ++i) fa[i] = *(const v4i*)(sa + i * 1024);
@@ -361,28 +366,35 @@ __global__ __launch_bounds__(384, 1) void gemm_i8_stream_regs_kernel(const GemmA
                     }
                     load_w(d, j, sw);
                 }
-                if (d % S == S - 1) slot = slot + 1 == NS ? 0 : slot + 1;
+                if (d % 2 == 1) slot = slot + 1 == NS ? 0 : slot + 1;
             }
         }
     }
 
-    // ---- the accumulators go through LDS (the ring is free now) so that the epilogue writes whole rows of the slab.
+    // ---- the accumulators meet in LDS (the ring is free now): the waves of K parity 0 store, those of parity 1 add
+    // (the same lane of the same unit group owns an element in both), and the epilogue writes whole rows of the slab.
     // 16x16 accumulator layout: lane l, register v holds row 4*(l >> 4) + v, column l & 15.
     int* red = (int*)smem;
     __syncthreads();  // everyone is done with the ring
-    if (wave < 4) {
-        const int col_l = lane & 15, row_l = (lane >> 4) * 4;
 #pragma unroll
-        for (int i = 0; i < MB; ++i)
+    for (int pass = 0; pass < 2; ++pass) {
+        if (wave < 6 && kp == pass) {
+            const int col_l = lane & 15, row_l = (lane >> 4) * 4;
 #pragma unroll
-            for (int j = 0; j < CNTW; ++j) {
-                const int u = wave + j * 4;
-                if (u >= nu) continue;  // a re-read unit
+            for (int i = 0; i < MB; ++i)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) red[(i * 16 + row_l + v) * PITCH + u * 16 + col_l] = acc[i][j][v];
-            }
+                for (int j = 0; j < CNTW; ++j) {
+                    const int u = ug + j * 3;
+                    if (u >= nu) continue;  // a re-read unit
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        int* dst = &red[(i * 16 + row_l + v) * PITCH + u * 16 + col_l];
+                        *dst = pass ? *dst + acc[i][j][v] : acc[i][j][v];
+                    }
+                }
+        }
+        __syncthreads();
     }
-    __syncthreads();
 
     // ---- epilogue: two neighbouring columns per thread
     const bool raw = q.to_i32 || q.gk > 1;
@@ -396,7 +408,7 @@ __global__ __launch_bounds__(384, 1) void gemm_i8_stream_regs_kernel(const GemmA
     }
     const int pairs = nu * 8;  // column pairs per row
     const int rows = p.M < MB * 16 ? p.M : MB * 16;
-    for (int idx = threadIdx.x; idx < rows * pairs; idx += 384) {
+    for (int idx = threadIdx.x; idx < rows * pairs; idx += 512) {
         const int row = idx / pairs, cp = idx - row * pairs;
         const int col = u0 * 16 + cp * 2;
         if (col >= p.N) continue;
@@ -463,10 +475,10 @@ bool make_stream_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool tiled
     const int na = M <= 16 ? 1 : M <= 32 ? 2 : M <= 64 ? 4 : 8;
     const int nk = (int)(K >> 6);
     // Tiled operands with more than 32 tokens go to the kernel with loader waves: a CU moves a little more per second
-    // there (fitted to the OPT-175B layers at 64 and 128 tokens), and a wave accumulates up to 4 of at most 16 units.
+    // there (fitted to the OPT-175B layers at 64 and 128 tokens), and a wave accumulates up to 4 of at most 12 units.
     const bool regs = tiled && na >= 4;
     const double cu_rate = regs ? 32e9 : 26e9, hbm_rate = regs ? 6.0e12 : 5.5e12, red_rate = 4e12, red_launch = 5e-6;
-    const int s_max = regs ? 16 : (na == 8 ? 24 : 16);  // widest slab the kernel shapes accumulate
+    const int s_max = regs ? kRegsMaxUnits : (na == 8 ? 24 : 16);  // widest slab the kernel shapes accumulate
     double best = 1e30, best_cu = 1e30;
     int best_gn = 0, best_gk = 0;
     for (int gk = 1; gk <= 8; ++gk) {
@@ -502,8 +514,9 @@ bool make_stream_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool tiled
     q.ksub = 1;
     q.regs = regs ? 1 : 0;
     if (regs) {
-        // a compute wave starts with 8 K steps of weight blocks; shorter ranges go to the LDS-ring kernel
-        if (nks < 8) return make_stream_plan(M, N, K, batch, false, out);
+        // a compute wave starts with its first 8 K steps of weight blocks (every other one of 16); shorter ranges go
+        // to the LDS-ring kernel
+        if (nks < 16) return make_stream_plan(M, N, K, batch, false, out);
     }
     if (!regs)
         for (int c = 4; c > 1; c >>= 1)
@@ -536,14 +549,15 @@ void sq_stream_gemm_launch(const GemmArgs& a, bool to_i32, bool bf16, bool tiled
     const dim3 grid((unsigned)(q.gn * q.gk)), block(256), block8(512);
     if (q.regs) {
         const int cnt = (q.units + q.gn - 1) / q.gn;  // widest slab
-#define SQ_R(MB, C) case C: sq_launch((gemm_i8_stream_regs_kernel<MB, C, true>), grid, dim3(384), 0, st, a, q); break;
-#define SQ_R16(MB) SQ_R(MB, 1) SQ_R(MB, 2) SQ_R(MB, 3) SQ_R(MB, 4) SQ_R(MB, 5) SQ_R(MB, 6) SQ_R(MB, 7) SQ_R(MB, 8) \
-                   SQ_R(MB, 9) SQ_R(MB, 10) SQ_R(MB, 11) SQ_R(MB, 12) SQ_R(MB, 13) SQ_R(MB, 14) SQ_R(MB, 15) SQ_R(MB, 16)
+#define SQ_R(MB, C) case C: sq_launch((gemm_i8_stream_regs_kernel<MB, C, true>), grid, block8, 0, st, a, q); break;
+#define SQ_R12(MB) SQ_R(MB, 1) SQ_R(MB, 2) SQ_R(MB, 3) SQ_R(MB, 4) SQ_R(MB, 5) SQ_R(MB, 6) SQ_R(MB, 7) SQ_R(MB, 8) \
+                   SQ_R(MB, 9) SQ_R(MB, 10) SQ_R(MB, 11) SQ_R(MB, 12)
+        static_assert(kRegsMaxUnits == 12, "launch table");
         switch (q.na) {
-            case 4: switch (cnt) { SQ_R16(4) default: break; } break;
-            default: switch (cnt) { SQ_R16(8) default: break; } break;
+            case 4: switch (cnt) { SQ_R12(4) default: break; } break;
+            default: switch (cnt) { SQ_R12(8) default: break; } break;
         }
-#undef SQ_R16
+#undef SQ_R12
 #undef SQ_R
         return;
     }

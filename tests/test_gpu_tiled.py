@@ -48,7 +48,7 @@ TILED_GEMM = [(1, 64, 16), (16, 768, 3072), (31, 320, 100), (33, 1024, 260), (64
               # weight streaming with more than 32 tokens (loader waves + weights through registers): the shortest K
               # range it takes and one below it, ragged tokens, slabs of unequal width, K steps that fill neither a
               # stage nor the unrolled body, a K split, the widest slabs
-              (33, 512, 4096), (40, 448, 4096), (100, 1088, 4112), (128, 4160, 8208), (65, 12288, 4096), (64, 2048, 36880),
+              (33, 1024, 4096), (40, 960, 4096), (100, 1088, 4112), (128, 4160, 8208), (65, 12288, 4096), (64, 2048, 36880),
               (128, 1024, 65536)]
 
 
