@@ -210,6 +210,16 @@ def softmax_quant_p(s_bits, dtype: int):
     return pq
 
 
+def softmax_quant_p_causal(s_bits, dtype: int):
+    """s [b, s_q, s_k] 16-bit scores; query i sees the keys j <= i + (s_k - s_q); returns the codes [b, s_q, s_k]."""
+    s = _c(bits16(s_bits), np.uint16)
+    b, s_q, s_k = s.shape
+    pq = np.empty(s.shape, np.int8)
+    _chk(lib().orc_softmax_quant_p_causal(_p(s), dtype, ctypes.c_int64(b), ctypes.c_int64(s_q), ctypes.c_int64(s_k), _p(pq)),
+         "softmax_quant_p_causal")
+    return pq
+
+
 def ln_quantize(x_bits, dtype: int, gamma_f, beta_f, eps: float = 1e-5):
     x = _c(bits16(x_bits), np.uint16)
     t, c_i = x.shape

@@ -394,6 +394,37 @@ int orc_softmax_quant_p(const uint16_t* s, int dtype, int64_t rows, int64_t cols
     return 0;
 }
 
+/* The same with a causal mask, as the decoder-only models of the paper apply it (the paper does not spell the
+   mask out; reading: query i of a head sees the keys j <= i + (s_k - s_q), i.e. the last query sees every key,
+   which is the usual rule when s_k - s_q earlier keys sit in a cache).  s, pq: [b, s_q, s_k].  Only the visible
+   scores enter the maximum and the sum; hidden positions get code 0.  Needs s_k >= s_q (every row sees a key). */
+int orc_softmax_quant_p_causal(const uint16_t* s, int dtype, int64_t b, int64_t s_q, int64_t s_k, int8_t* pq)
+{
+    if (!s || !pq) return 1;
+    if (b <= 0 || s_q <= 0 || s_k < s_q) return 2;
+    const int64_t off = s_k - s_q;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < b * s_q; ++r) {
+        const int64_t i = r % s_q;
+        const int64_t vis = i + off + 1; /* number of visible keys */
+        const uint16_t* row = s + r * s_k;
+        double mx = -INFINITY;
+        for (int64_t j = 0; j < vis; ++j) {
+            double z = (double)load16(row + j, dtype);
+            if (z > mx) mx = z;
+        }
+        double den = 0.0;
+        for (int64_t j = 0; j < vis; ++j) den += exp((double)load16(row + j, dtype) - mx);
+        for (int64_t j = 0; j < vis; ++j) {
+            double p = exp((double)load16(row + j, dtype) - mx) / den;
+            float p16 = load16(&(uint16_t){store16((float)p, dtype)}, dtype);
+            pq[r * s_k + j] = round_code(p16 * 127.0f);
+        }
+        for (int64_t j = vis; j < s_k; ++j) pq[r * s_k + j] = 0;
+    }
+    return 0;
+}
+
 /* LayerNorm whose affine parameters already carry 1/s (gamma' = gamma * inv_s, beta' = beta * inv_s,
    folded offline), followed by per-token dynamic quantization.  Statistics in fp64 over the row;
    x_hat = fl32( (x - mu) / sqrt(var + eps) * gamma'_j + beta'_j ). */

@@ -407,6 +407,56 @@ def test_softmax_quant_special_cases_bf16():
     assert np.array_equal(oracle.softmax_quant_p(si, BF16), oracle.softmax_quant_p(sj, BF16))
 
 
+def test_softmax_quant_causal_pins():
+    """Causal variant of the softmax + P quantization (Sec. 4 keeps the softmax in the 16-bit type; the mask itself is
+    the usual rule of a decoder: query i sees the keys j <= i + (s_k - s_q)).  Pinned by closed forms, by the textbook
+    softmax of the truncated rows, and by the unmasked function on scores that hold -inf where the mask hides a key."""
+    from scipy.special import softmax
+    # uniform scores, square: row i sees i + 1 keys with p = 1 / (i + 1) each
+    pq = oracle.softmax_quant_p_causal(np.zeros((1, 6, 6), np.float16), F16)
+    for i in range(6):
+        p16 = np.float16(1.0 / (i + 1))
+        code = int(np.rint(np.float32(p16) * np.float32(127.0)))
+        assert pq[0, i].tolist() == [code] * (i + 1) + [0] * (5 - i)
+    assert pq[0, 0, 0] == 127 and pq[0, 1, 0] == 64 and pq[0, 3, 0] == 32
+    # four cached keys in front (s_k - s_q = 4): the first query sees five keys, the last one all of them
+    pq = oracle.softmax_quant_p_causal(np.zeros((2, 3, 7), np.float16), F16)
+    assert pq[1].tolist() == [[25] * 5 + [0] * 2, [21] * 6 + [0], [18] * 7]
+    # a hidden key never matters, however large its score
+    s = np.zeros((1, 4, 4), np.float16)
+    s[0, 1, 3] = 30.0
+    s[0, 2, 2] = 30.0  # visible to query 2: takes the whole row
+    pq = oracle.softmax_quant_p_causal(s, F16)
+    assert pq[0, 1].tolist() == [64, 64, 0, 0] and pq[0, 2].tolist() == [0, 0, 127, 0]
+    # random scores, both 16-bit types: textbook softmax over the visible prefix of every row
+    rng = np.random.default_rng(43)
+    b, s_q, s_k = 3, 37, 53
+    off = s_k - s_q
+    s64 = np.rint(rng.standard_normal((b, s_q, s_k)) * 3 * 8) / 8  # exact in fp16 and in bf16
+    for dtype in (F16, BF16):
+        bits = s64.astype(np.float16) if dtype == F16 else _bf16_bits(s64.astype(np.float32)).reshape(s64.shape)
+        got = oracle.softmax_quant_p_causal(bits, dtype)
+        masked = s64.copy()
+        for i in range(s_q):
+            masked[:, i, i + off + 1:] = -np.inf
+        p = softmax(masked, axis=-1)
+        if dtype == F16:
+            p16 = p.astype(np.float16).astype(np.float32)
+        else:
+            import torch
+            p16 = torch.from_numpy(p).to(torch.bfloat16).to(torch.float32).numpy()
+        want = np.rint(p16 * np.float32(127.0)).astype(np.int8)
+        assert np.array_equal(got, want)
+        for i in range(s_q):
+            assert not got[:, i, i + off + 1:].any()
+        # the unmasked function fed with -inf at the hidden positions agrees
+        mb = masked.astype(np.float16) if dtype == F16 else _bf16_bits(masked.astype(np.float32)).reshape(masked.shape)
+        assert np.array_equal(oracle.softmax_quant_p(mb, dtype), got)
+    # the mask is bottom-right aligned: the last query's row equals the unmasked softmax of that row
+    last = oracle.softmax_quant_p(s64[:, -1:, :].astype(np.float16), F16)
+    assert np.array_equal(oracle.softmax_quant_p_causal(s64.astype(np.float16), F16)[:, -1:, :], last)
+
+
 def test_ln_quantize_properties():
     rng = np.random.default_rng(51)
     t, c_i = 6, 512
