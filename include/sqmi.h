@@ -204,6 +204,18 @@ sq_status sq_w8a8_attention(const int8_t* q, const int8_t* k, const int8_t* v, f
                             int64_t stride_q, int64_t stride_k, int64_t stride_v, int64_t stride_o,
                             int8_t* p_codes, void* stream);
 
+/* The same block with the causal mask of a decoder (the models of Sec. 5 are decoder-only; the paper does not spell
+ * the mask out): query i sees the keys j <= i + (s_k - s_q), so with s_k = s_q every query sees the keys up to its
+ * own position, and with s_k > s_q the first s_k - s_q keys (a cache of earlier tokens) are seen by all.  Hidden keys
+ * take no part in the maximum or the sum of the softmax and get probability code 0; key tiles no row of a workgroup
+ * sees are skipped, which is where the time goes down.  Arguments, layouts and limits as sq_w8a8_attention, plus
+ * s_k >= s_q (SQ_ERR_SHAPE otherwise: the first queries would see nothing).  Equals sq_w8a8_bmm, then
+ * sq_softmax_quant_p on scores that hold -inf at the hidden positions, then sq_w8a8_bmm. */
+sq_status sq_w8a8_attention_causal(const int8_t* q, const int8_t* k, const int8_t* v, float alpha1, float alpha2,
+                                   void* o, sq_dtype out, int64_t b, int64_t s_q, int64_t s_k, int64_t d,
+                                   int64_t stride_q, int64_t stride_k, int64_t stride_v, int64_t stride_o,
+                                   int8_t* p_codes, void* stream);
+
 /* Row softmax kept in 16-bit floating point (Sec. 4 keeps Softmax in FP16) followed by quantization
  * of the probabilities with the fixed step 1/127: pq = round(p * 127) in [0, 127].
  * s: device [rows, cols] 16-bit scores, packed; pq: device int8 [rows, cols].

@@ -24,7 +24,7 @@ EXPORTS = (
     "sq_status_string", "sq_smooth_scales", "sq_act_absmax_per_channel", "sq_weight_absmax_per_in_channel",
     "sq_prepare_weight", "sq_quantize_act", "sq_w8a8_linear", "sq_w8a8_linear_q8", "sq_i8_gemm_i32", "sq_w8a8_bmm",
     "sq_softmax_quant_p", "sq_ln_quantize", "sq_workspace_bytes", "sq_tiled_bytes", "sq_probe_mfma_i8",
-    "sq_w8a8_linear_noalloc", "sq_static_scratch_bytes", "sq_w8a8_attention",
+    "sq_w8a8_linear_noalloc", "sq_static_scratch_bytes", "sq_w8a8_attention", "sq_w8a8_attention_causal",
 )
 
 
@@ -60,6 +60,7 @@ def lib() -> ctypes.CDLL:
         L.sq_i8_gemm_i32.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, ctypes.c_size_t, vp]
         L.sq_w8a8_bmm.argtypes = [vp, vp, i32, f32, vp, i32, i64, i64, i64, i64, i64, i64, i64, vp]
         L.sq_w8a8_attention.argtypes = [vp, vp, vp, f32, f32, vp, i32, i64, i64, i64, i64, i64, i64, i64, i64, vp, vp]
+        L.sq_w8a8_attention_causal.argtypes = L.sq_w8a8_attention.argtypes
         L.sq_probe_mfma_i8.argtypes = [vp, ctypes.c_size_t, i32, i32, vp, vp]
         L.sq_softmax_quant_p.argtypes = [vp, i32, i64, i64, vp, vp]
         L.sq_ln_quantize.argtypes = [vp, i32, i64, i64, vp, vp, f32, vp, vp, i32, vp]
@@ -295,9 +296,10 @@ def w8a8_bmm(a: torch.Tensor, bm: torch.Tensor, trans_b: bool, alpha: float, out
 
 
 def w8a8_attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, alpha1: float, alpha2: float, out_dtype, out=None,
-                   p_codes: torch.Tensor | None = None) -> torch.Tensor:
+                   p_codes: torch.Tensor | None = None, causal: bool = False) -> torch.Tensor:
     """Fused INT8 attention: q [b, s_q, d], k and v [b, s_k, d] int8 -> o [b, s_q, d].  ``p_codes`` (int8
-    [b, s_q, s_k]) optionally receives the probability codes the kernel formed."""
+    [b, s_q, s_k]) optionally receives the probability codes the kernel formed.  ``causal`` selects
+    sq_w8a8_attention_causal (query i sees the keys j <= i + (s_k - s_q))."""
     b, s_q, d = q.shape
     s_k = k.shape[1]
     if tuple(k.shape) != (b, s_k, d) or tuple(v.shape) != (b, s_k, d):
@@ -305,9 +307,10 @@ def w8a8_attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, alpha1: fl
     o = torch.empty((b, s_q, d), dtype=out_dtype, device=q.device) if out is None else out
     if p_codes is not None and tuple(p_codes.shape) != (b, s_q, s_k):
         raise SqmiError("p_codes must be [b, s_q, s_k]")
-    _check(lib().sq_w8a8_attention(_dev(q, torch.int8, "q"), _dev(k, torch.int8, "k"), _dev(v, torch.int8, "v"), alpha1, alpha2,
-                                   _dev(o, out_dtype, "o"), _dt(o), b, s_q, s_k, d, s_q * d, s_k * d, s_k * d, s_q * d,
-                                   _opt(p_codes, torch.int8, "p_codes"), _stream()), "sq_w8a8_attention")
+    fn = lib().sq_w8a8_attention_causal if causal else lib().sq_w8a8_attention
+    _check(fn(_dev(q, torch.int8, "q"), _dev(k, torch.int8, "k"), _dev(v, torch.int8, "v"), alpha1, alpha2,
+              _dev(o, out_dtype, "o"), _dt(o), b, s_q, s_k, d, s_q * d, s_k * d, s_k * d, s_q * d,
+              _opt(p_codes, torch.int8, "p_codes"), _stream()), "sq_w8a8_attention_causal" if causal else "sq_w8a8_attention")
     return o
 
 

@@ -166,3 +166,8 @@ def test_fused_attention_argument_errors_before_any_launch():
     assert L.sq_w8a8_attention(*args(d=96)) == 4         # head dimension 64 or 128
     assert L.sq_w8a8_attention(*args(a1=-1.0)) == 4      # alpha1 must be positive
     assert L.sq_w8a8_attention(*args(q=0x1004)) == 3
+    # the causal form: same checks, and the queries may not outnumber the keys
+    assert L.sq_w8a8_attention_causal(*args(q=None)) == 1
+    assert L.sq_w8a8_attention_causal(*args(s_k=100)) == 3
+    assert L.sq_w8a8_attention_causal(*args(d=96)) == 4
+    assert L.sq_w8a8_attention_causal(*args(s_k=48)) == 2  # 64 queries, 48 keys: the first queries would see no key
