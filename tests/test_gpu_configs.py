@@ -193,6 +193,19 @@ def test_config4_int8_attention_bmms():
     assert int(d_all.max()) <= 1 and float((d_all != 0).float().mean()) <= 1e-3
     del d_all
     assert int(pq_f.min()) >= 0  # every code was written
+    _progress("config 4: the fused kernel with the causal mask")
+    pq_f.fill_(-128)
+    o_c = sq.w8a8_attention(codes[0], codes[1], codes[2], alpha1, alpha2, torch.float16, p_codes=pq_f, causal=True)
+    for h in heads:
+        sc_ref = oracle.w8a8_bmm(codes[0][h:h + 1].cpu().numpy(), codes[1][h:h + 1].cpu().numpy(), True, alpha1, F16)
+        ref = oracle.softmax_quant_p_causal(sc_ref, F16)[0].astype(np.int32)
+        got = pq_f[h].cpu().numpy().astype(np.int32)
+        diff = np.abs(got - ref)
+        assert got.min() >= 0 and diff.max() <= 1 and (diff != 0).mean() <= 1e-3, f"causal: codes of head {h}"
+        assert not np.triu(got, 1).any(), f"causal: a hidden key of head {h} got a probability"
+        o_ref = oracle.w8a8_bmm(pq_f[h:h + 1].cpu().numpy(), codes[2][h:h + 1].cpu().numpy(), False, alpha2, F16)
+        assert_identical_16(ulp_distance(bits_from_dev(o_c[h]), o_ref[0]), f"causal: output of head {h}")
+    assert int(pq_f.min()) >= 0 and not bool(pq_f.triu(1).any())  # all heads: every code written, nothing above the diagonal
 
 
 def test_config5_opt66b_decoder_layer_chain():
