@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include <tuple>
+#include <utility>
 #include <type_traits>
 
 #include "sqmi.h"
@@ -15,6 +16,14 @@ typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 
 #define SQ_DEVICE static __device__ __forceinline__
+
+// f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{}): a loop whose index is a constant
+// expression inside the body (builtins that take immediates, register arrays indexed modulo something).
+template <int... I, class F> SQ_DEVICE void static_for_impl(std::integer_sequence<int, I...>, F&& f)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F> SQ_DEVICE void static_for(F&& f) { static_for_impl(std::make_integer_sequence<int, N>{}, f); }
 
 // ---- 16-bit formats.  fp16 uses the hardware converts (round-to-nearest-even in the default
 // mode); bf16 is widened by a shift and narrowed with the integer nearest-even rule.

@@ -49,19 +49,27 @@ enum { LAY_ROWS = 0, LAY_BT = 1, LAY_TILED = 2 };
 // buffers, no refills, no barriers in the K loop.  Used for attention scores (K = head_dim), where the
 // kernel is bound by writing its output and several small workgroups per CU (OCC) overlap each other's
 // load, MFMA and store phases.
-template <int BM, int BN, int WGM, int WGN, int NSTAGE, int EPI, bool BF16, int LAY, int OCC = 1, bool ONESHOT = false>
+//
+// MF selects the MFMA shape: 32 = v_mfma_i32_32x32x32_i8 (two per 64-byte K step and accumulator block), 16 =
+// v_mfma_i32_16x16x64_i8 (one per K step; a 1 KB LDS block is exactly one operand).  On quantized operands the matrix
+// pipes draw less power per multiply-accumulate in the 16x16x64 shape (a register-fed loop of it sustains 4.1-4.2 POP/s
+// under the socket's power cap where the 32x32x32 shape sustains 3.6), and the compute-bound tiles run at that cap.
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, int EPI, bool BF16, int LAY, int OCC = 1, bool ONESHOT = false, int MF = 32>
 __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmArgs p)
 {
     constexpr bool BT = LAY == LAY_BT, TILED = LAY == LAY_TILED;
     constexpr int NW = WGM * WGN, BK = 64;
-    constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / 32, NI = WN / 32;
+    constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / MF, NI = WN / MF;
+    constexpr int AV = MF * MF / 64;  // accumulator registers per block
+    constexpr int QG = AV / 4;        // runs of four neighbouring output columns a lane holds per block
+    static_assert(MF == 32 || (MF == 16 && !BT && !ONESHOT && MI == 4 && NI % 4 == 0), "MFMA shape");
     constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE = A_BYTES + B_BYTES;
     constexpr int RBA = BM / 16, RBB = BN / 16;  // 16-row blocks per operand tile
     constexpr int SA = (RBA + NW - 1) / NW, SB = (RBB + NW - 1) / NW;  // BT: SB raw 1 KB blocks of the [64, BN] B tile
     constexpr int KR = BT ? BN / 16 : 0;  // BT: each lane transposes a KR (k) x 4 (n) byte block per stage
     constexpr int LPS = SA + SB;          // vector-memory loads per wave per stage
     static_assert(!BT || (NW == 4 && BN == 128 && RBB % NW == 0), "transposed-B path assumes 256 lanes and 128 columns");
-    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile must be a multiple of the 32x32 MFMA");
+    static_assert(WM % MF == 0 && WN % MF == 0, "wave tile must be a multiple of the MFMA block");
     static_assert(NSTAGE >= (BT ? 4 : 3) && (NSTAGE - 2) * LPS <= 63, "pipeline depth exceeds the 6-bit vmcnt");
     static_assert(NSTAGE * STAGE <= 160 * 1024, "LDS budget");
     // The epilogue stages the 16-bit tile in LDS; a tile too large for that goes in EG groups of GR rows.
@@ -235,19 +243,24 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
     // ---- MFMA operand fragments.  For the 32x32x32 MFMA lane l feeds row (l & 31) with the 16
     // bytes of K-chunk kk*2 + (l >> 5) of the 64-wide K step; chunk c of row r sits at position
     // c ^ swz(r), and kk only flips bit 1 of the position: byte address ^ 32.
+    // For the 16x16x64 MFMA lane l feeds row (l & 15) with the 16 bytes of K-chunk (l >> 4): one 1 KB block, whole.
     const int frow = lane & 15;
-    const int lane_off = ((lane & 31) >> 4) * 1024 + frow * 64 + (((lane >> 5) ^ swz(frow)) * 16);
+    const int lane_off = MF == 32 ? ((lane & 31) >> 4) * 1024 + frow * 64 + (((lane >> 5) ^ swz(frow)) * 16)
+                                  : frow * 64 + (((lane >> 4) ^ swz(frow)) * 16);
     const int fragA0 = wm * (WM / 16) * 1024 + lane_off;
     const int fragB0 = (BT ? 0 : A_BYTES) + wn * (WN / 16) * 1024 + lane_off;
 
-    v4i fa0[MI], fb0[NI], fa1[MI], fb1[NI];
-    v16i acc[MI][NI];
+    typedef int acc_t __attribute__((ext_vector_type(AV)));
+    acc_t acc[MI][NI];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+            for (int v = 0; v < AV; ++v) acc[i][j][v] = 0;
+
+    if constexpr (MF == 32) {
+    v4i fa0[MI], fb0[NI], fa1[MI], fb1[NI];
 
     auto read_frags = [&](v4i(&fa)[MI], v4i(&fb)[NI], int buf, int kk, int op_buf) {
         const char* sa = smem + buf * STAGE + (fragA0 ^ (kk * 32));
@@ -347,24 +360,112 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
     }
     mfma_all(fa0, fb0);
     mfma_all(fa1, fb1);
+    } else {
+    // ---- 16x16x64 shape.  A wave owns 64 rows x WN columns.  Its four A fragments of a K step stay in registers for the
+    // whole step (the next step's four are read meanwhile into a second set); the NI B fragments come in NP parts of
+    // two, double buffered: while the 8 MFMAs of a part issue, the two fragments of the next part are read.
+    // Per step 4 + NI reads of 1 KB and 4 NI MFMAs.  The barrier that publishes stage it + 1 sits in front of part
+    // NP / 2; the reads that belong to the next step (its A fragments, its first part of B) come after it.
+    constexpr int NQ = 2, NP = NI / NQ, PB = NP / 2;
+    static_assert(NP % 2 == 0 && (NP - PB == 2 || NP - PB == 3), "parts of a K step");
+    v4i fa[2][MI], fbq[2][NQ];
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; ++s) issue_stage(s < nk ? s : nk - 1, s);
+    wait_vmcnt_imm<(NSTAGE - 2) * LPS>();
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int i = 0; i < MI; ++i) fa[0][i] = *(const v4i*)(smem + fragA0 + i * 1024);
+#pragma unroll
+    for (int k = 0; k < NQ; ++k) fbq[0][k] = *(const v4i*)(smem + fragB0 + k * 1024);
+
+    // Every step is the same code: the last one also reads "next" fragments (from a buffer that holds an old stage:
+    // valid LDS, values never used) and refills a buffer nobody reads.  The host sends only K ranges of an even number
+    // of whole steps here (K % 128 == 0, no K split), so the loop runs in pairs and there is no second copy of the step
+    // outside it (with one, the register allocation of the epilogue spilled hundreds of registers per lane).
+    auto step = [&](v4i(&cur)[MI], v4i(&nxt)[MI], int it, int buf) {
+        const int nbuf = buf + 1 == NSTAGE ? 0 : buf + 1;
+        const char* sb = smem + buf * STAGE + fragB0;
+        const char* sn = smem + nbuf * STAGE;
+        // the stage this step fetches (past the end of the K range the last one again), into the buffer of step it - 1
+        const int kt = it + NSTAGE - 1 < nk ? it + NSTAGE - 1 : nk - 1;
+        const int8_t* ga = Ab + (int64_t)kt * KSTEP;
+        const int8_t* gb = Bb + (int64_t)kt * KSTEP;
+        char* refill = smem + (buf == 0 ? NSTAGE - 1 : buf - 1) * STAGE;
+        static_for<NP>([&](auto Q_) {
+            constexpr int q = decltype(Q_)::value;
+            if constexpr (q == PB) {
+                wait_vmcnt_imm<(NSTAGE - 3) * LPS>();
+                __builtin_amdgcn_s_barrier();
+            }
+            // next step's A fragments: two in the first part behind the barrier, the rest over the parts that follow
+            constexpr int pa = q - PB;  // parts behind the barrier so far
+            constexpr int an0 = pa <= 0 ? 0 : (NP - PB == 2 ? 2 * pa : pa + 1);
+            constexpr int an_cnt = pa < 0 ? 0 : (NP - PB == 2 ? 2 : (pa == 0 ? 2 : 1));
+            // The part in the instruction stream, fixed by scheduling fences: its first MFMA (in front of it the wait
+            // for this part's fragments, which is exact there: nothing younger is in flight), then the reads of the
+            // next part and, behind the barrier, the stage's global->LDS loads, then the other seven MFMAs, which
+            // cover the latency of those reads.
+            acc[0][q * NQ] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fbq[q & 1][0], cur[0], acc[0][q * NQ], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (q >= PB) {
+                // the stage's loads (the first SA are A blocks, the others B blocks), spread over the parts behind the
+                // barrier: issued in one burst they cost an eighth more time per step
+                constexpr int per = (LPS + NP - PB - 1) / (NP - PB), i0 = (q - PB) * per, i1 = i0 + per < LPS ? i0 + per : LPS;
+                static_for<(i1 > i0 ? i1 - i0 : 0)>([&](auto D_) {
+                    constexpr int i = i0 + decltype(D_)::value;
+                    // (the offset is made opaque here so that its widening to 64 bits stays next to the load: hoisted out
+                    // of the loop it costs a register pair per load and the scalar-base addressing form)
+                    uint32_t o = i < SA ? offA[i < SA ? i : 0] : offB[i < SA ? 0 : i - SA];
+                    asm volatile("" : "+v"(o));
+                    if constexpr (i < SA) __builtin_amdgcn_global_load_lds(GPTR(ga + o), LPTR(refill + ldsA[i]), 16, 0, 0);
+                    else __builtin_amdgcn_global_load_lds(GPTR(gb + o), LPTR(refill + ldsB[i - SA]), 16, 0, 0);
+                });
+            }
+            if constexpr (q < NP - 1) {
+#pragma unroll
+                for (int k = 0; k < NQ; ++k) fbq[(q + 1) & 1][k] = *(const v4i*)(sb + ((q + 1) * NQ + k) * 1024);
+            } else {
+#pragma unroll
+                for (int k = 0; k < NQ; ++k) fbq[0][k] = *(const v4i*)(sn + fragB0 + k * 1024);
+            }
+#pragma unroll
+            for (int k = 0; k < an_cnt; ++k) nxt[an0 + k] = *(const v4i*)(sn + fragA0 + (an0 + k) * 1024);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < NQ; ++k)
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+                    if (k + i > 0)
+                        acc[i][q * NQ + k] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fbq[q & 1][k], cur[i], acc[i][q * NQ + k], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+    int buf = 0;
+    for (int it = 0; it < nk; it += 2) {
+        step(fa[0], fa[1], it, buf);
+        buf = buf + 1 == NSTAGE ? 0 : buf + 1;
+        step(fa[1], fa[0], it + 1, buf);
+        buf = buf + 1 == NSTAGE ? 0 : buf + 1;
+    }
+    }
     wait_vmcnt_imm<0>();  // the refills issued past the end of the K range have landed
 
     // ---- epilogue.  Accumulator block (i, j) is the transposed 32x32 output block: lane l, register v
     // holds output row (l & 31), column 8*(v/4) + 4*(l >> 5) + (v & 3) of the block, i.e. registers
-    // 4g .. 4g+3 are four neighbouring columns of one row.
-    const int row_l = lane & 31, col_l = (lane >> 5) * 4;
+    // 4g .. 4g+3 are four neighbouring columns of one row.  (16x16 blocks: row (l & 15), columns 4*(l >> 4) + v.)
+    const int row_l = lane & (MF - 1), col_l = (lane >> (MF == 32 ? 5 : 4)) * 4;
     if constexpr (EPI == EPI_I32) {
         int32_t* out = p.acc_out + ((int64_t)split * p.M) * p.N;
         const bool vec4 = (p.N & 3) == 0;  // 16-byte stores stay aligned and inside the row
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
-            const int row = m0 + wm * WM + i * 32 + row_l;
+            const int row = m0 + wm * WM + i * MF + row_l;
             if (row < p.M) {
 #pragma unroll
                 for (int j = 0; j < NI; ++j)
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int col = n0 + wn * WN + j * 32 + 8 * g + col_l;
+                    for (int g = 0; g < QG; ++g) {
+                        const int col = n0 + wn * WN + j * MF + 8 * g + col_l;
                         int32_t* dst = out + (int64_t)row * p.N + col;
                         if (vec4 && col < p.N) {
                             *(v4i*)dst = v4i{acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
@@ -396,8 +497,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
         for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int j = 0; j < NI; ++j) {
-                typedef float v16f __attribute__((ext_vector_type(16)));
-                acc[i][j] = __builtin_bit_cast(v16i, __builtin_convertvector(acc[i][j], v16f));
+                typedef float accf_t __attribute__((ext_vector_type(AV)));
+                acc[i][j] = __builtin_bit_cast(acc_t, __builtin_convertvector(acc[i][j], accf_t));
             }
         float rq = 0.0f;
         if (p.q8_step) {
@@ -439,8 +540,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
             constexpr bool has_bias = decltype(HB)::value, relu = decltype(RL)::value, has_res = decltype(HR)::value;
 #pragma unroll
             for (int i = 0; i < MI; ++i) {
-                if (EG > 1 && (wm * WM + i * 32) / GR != eg) continue;  // rows of another group
-                const int lrow = wm * WM + i * 32 + row_l - g0 + opaque0;
+                if (EG > 1 && (wm * WM + i * MF) / GR != eg) continue;  // rows of another group
+                const int lrow = wm * WM + i * MF + row_l - g0 + opaque0;
                 const int row = m0 + g0 + lrow;
                 const float xrow = p.x_scale ? (p.per_token ? p.x_scale[row < p.M ? row : p.M - 1] : xs0) : 0.0f;
                 float c;
@@ -449,8 +550,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
 #pragma unroll
                 for (int j = 0; j < NI; ++j)
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int lcol = wn * WN + j * 32 + 8 * g + col_l + opaque0;
+                    for (int g = 0; g < QG; ++g) {
+                        const int lcol = wn * WN + j * MF + 8 * g + col_l + opaque0;
                         float cq[4] = {c, c, c, c};
                         if (p.w_per_channel) {  // c = Delta_X[row] * Delta_W[col]
 #pragma unroll
@@ -561,6 +662,7 @@ struct Plan {
                  // 7: 128x128, three workgroups per CU (short K: the output stream dominates)
                  // 8: 128x128, K <= 128 fetched in one go, four workgroups per CU
                  // 9: 256x384 (a round of tiles saved on wide outputs)
+                 // 10, 11: 256x256 and 256x384 with the 16x16x64 MFMA
     int bm, bn;
     int splits, iters_per_split;
     int tiles_m, tiles_n;
@@ -593,26 +695,26 @@ Plan make_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split,
         allow_split = false;
     }
     else if (M > 128) {
-        // Compute-bound shapes: pick the tile width whose last round of tiles wastes the fewest CUs.  Time is
-        // proportional to rounds x cost of one tile; a 256x192 tile costs 0.875 of a 256x256 one (measured:
-        // its K loop runs 16 % slower per multiply-accumulate, fewer MFMAs per operand fragment read).
+        // Compute-bound shapes: time = rounds of tiles over the 256 CUs x cost of one tile; pick the cheapest width.
+        // Cost of a tile in microseconds, measured on quantized Gaussian operands (the clock that the power cap allows
+        // is part of these figures): K steps x 0.59 + 6 (256x192: fewer MFMAs per operand fragment read), x 0.70 + 18
+        // (256x256), x 1.12 + 8 (256x384: 192 accumulator registers per lane, the whole 160 KB of LDS, the epilogue in
+        // two halves) with the 32x32x32 MFMA; the 256- and 384-wide tiles also exist with the 16x16x64 MFMA, which
+        // draws less power per multiply-accumulate: x 0.63 + 18 and x 1.03 + 8.  That form needs an even number of
+        // whole K steps and no K split (see the kernel); other shapes keep the 32x32x32 form.
         pl.cfg = 0;
         pl.bm = 256;
+        const bool mf16 = (K & 127) == 0;
         const int64_t tm = (M + 255) / 256;
         const int64_t rounds256 = (tm * ((N + 255) / 256) * batch + kNumCU - 1) / kNumCU;
         const int64_t rounds192 = (tm * ((N + 191) / 192) * batch + kNumCU - 1) / kNumCU;
-        const bool use192 = rounds192 * 224 < rounds256 * 256;
-        if (use192) { pl.cfg = 6; pl.bn = 192; }
-        // 256x384 tiles (192 accumulator registers per lane, the whole 160 KB of LDS, epilogue in two halves): fewer
-        // operand bytes per multiply-accumulate and fewer rounds of tiles.  Measured per tile on quantized Gaussian
-        // operands (the clock the power cap allows is part of these figures), in microseconds: K steps x 0.59 + 6
-        // (192 wide), x 0.70 + 18 (256), x 1.12 + 8 (384).  Taken where that model promises at least 2 %: with 2048
-        // tokens all four OPT-175B layers (3 rounds instead of 5, 1 instead of 2, 4 instead of 6), with 4096 tokens
-        // of OPT-66B only FC1.
         const int64_t rounds384 = (tm * ((N + 383) / 384) * batch + kNumCU - 1) / kNumCU;
         const double nks = (double)((K + 63) / 64);
-        const double t_now = use192 ? rounds192 * (nks * 0.588 + 6.0) : rounds256 * (nks * 0.70 + 18.0);
-        const double t384 = rounds384 * (nks * 1.12 + 8.0);
+        const double t192 = rounds192 * (nks * 0.588 + 6.0);
+        const double t256 = rounds256 * (nks * (mf16 ? 0.63 : 0.70) + 18.0);
+        const double t384 = rounds384 * (nks * (mf16 ? 1.03 : 1.12) + 8.0);
+        double t_now = t256;
+        if (t192 < t256) { pl.cfg = 6; pl.bn = 192; t_now = t192; }
         if (t384 < 0.98 * t_now) { pl.cfg = 9; pl.bn = 384; }
     }
     else if (M > 64) { pl.cfg = 1; pl.bm = 128; }
@@ -648,6 +750,10 @@ Plan make_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split,
     splits = (nk + per - 1) / per;  // no empty split
     pl.splits = splits;
     pl.iters_per_split = per;
+    if ((K & 127) == 0 && splits == 1) {  // the 16x16x64 form of the tile
+        if (pl.cfg == 0) pl.cfg = 10;
+        if (pl.cfg == 9) pl.cfg = 11;
+    }
     return pl;
 }
 
@@ -655,11 +761,12 @@ template <int EPI, bool BF16>
 void launch_cfg(const Plan& pl, const GemmArgs& a, int batch, hipStream_t st, bool tiled)
 {
     dim3 grid((unsigned)(pl.tiles_m * pl.tiles_n * pl.splits), (unsigned)batch);
-#define SQ_LAUNCH(BM, BN, WGM, WGN, NST)                                                                          \
+#define SQ_LAUNCH_MF(BM, BN, WGM, WGN, NST, MF)                                                                   \
     do {                                                                                                          \
-        if (tiled) sq_launch((gemm_i8_kernel<BM, BN, WGM, WGN, NST, EPI, BF16, LAY_TILED>), grid, dim3(WGM * WGN * 64), 0, st, a); \
-        else sq_launch((gemm_i8_kernel<BM, BN, WGM, WGN, NST, EPI, BF16, LAY_ROWS>), grid, dim3(WGM * WGN * 64), 0, st, a); \
+        if (tiled) sq_launch((gemm_i8_kernel<BM, BN, WGM, WGN, NST, EPI, BF16, LAY_TILED, 1, false, MF>), grid, dim3(WGM * WGN * 64), 0, st, a); \
+        else sq_launch((gemm_i8_kernel<BM, BN, WGM, WGN, NST, EPI, BF16, LAY_ROWS, 1, false, MF>), grid, dim3(WGM * WGN * 64), 0, st, a); \
     } while (0)
+#define SQ_LAUNCH(BM, BN, WGM, WGN, NST) SQ_LAUNCH_MF(BM, BN, WGM, WGN, NST, 32)
     switch (pl.cfg) {
         case 0: SQ_LAUNCH(256, 256, 2, 4, 4); break;
         case 1: SQ_LAUNCH(128, 256, 1, 4, 6); break;
@@ -667,6 +774,8 @@ void launch_cfg(const Plan& pl, const GemmArgs& a, int batch, hipStream_t st, bo
         case 3: SQ_LAUNCH(32, 256, 1, 4, 8); break;
         case 6: SQ_LAUNCH(256, 192, 4, 2, 4); break;
         case 9: SQ_LAUNCH(256, 384, 2, 4, 4); break;
+        case 10: SQ_LAUNCH_MF(256, 256, 4, 2, 4, 16); break;
+        case 11: SQ_LAUNCH_MF(256, 384, 4, 2, 4, 16); break;
         case 8:
             if (tiled) sq_launch((gemm_i8_kernel<128, 128, 2, 2, 3, EPI, BF16, LAY_TILED, 4, true>), grid, dim3(256), 0, st, a);
             else sq_launch((gemm_i8_kernel<128, 128, 2, 2, 3, EPI, BF16, LAY_ROWS, 4, true>), grid, dim3(256), 0, st, a);
@@ -682,6 +791,7 @@ void launch_cfg(const Plan& pl, const GemmArgs& a, int batch, hipStream_t st, bo
             break;
     }
 #undef SQ_LAUNCH
+#undef SQ_LAUNCH_MF
 }
 
 // allow_split = false: the caller has no workspace to offer (sq_w8a8_bmm), so only plans that finish in one kernel
