@@ -512,14 +512,14 @@ def main():
         "config": {"workload": f"opt175b_linears_hidden12288_M{t}: qkv+out_proj+fc1+fc2, per-token dynamic act, "
                                "per-tensor weight, bf16 out, 0.5% outlier channels x80, alpha 0.5"},
         "pct_int8_mfma_peak": round(100.0 * tops / PEAK_INT8_TOPS, 2),
-        "roofline": {"bound": "mfma", "kernel": "gemm_i8_kernel (256x384 / 256x256 tiles, INT8 MFMA GEMM + dequant epilogue)",
+        "roofline": {"bound": "mfma", "kernel": "gemm_i8_kernel (256x384 tiles, 16x16x64 INT8 MFMA, GEMM + dequant epilogue)",
                      "achieved": round(gemm_tops, 2), "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s",
                      "frac": round(gemm_tops / PEAK_INT8_TOPS, 4), "traffic": traffic, "traffic_source": traffic_src,
                      "mfma_only_loop_tops": round(mfma_only_tops, 1),
                      "frac_of_mfma_only_loop": round(gemm_tops / mfma_only_tops, 4),
                      "note": "int8 multiply-accumulate counted as 2 ops; achieved = sum of 2*T*C_i*C_o over the four "
                              "layers / sum of their median GEMM launch durations (HIP events on the launch stream); "
-                             "mfma_only_loop_tops = register-fed MFMA loop on the same weight codes, 2048 workgroups x 8 "
+                             "mfma_only_loop_tops = register-fed 16x16x64 MFMA loop on the same weight codes, 2048 workgroups x 8 "
                              "waves: what the matrix pipes sustain at the clock the chip holds under this load (the "
                              "clock is set by the power the operands' bit activity draws: `bench.py --power-probe`)"},
         "per_layer_us": {L["name"]: {"quantize": round(L["quant_us"], 1), "quantize_min": round(L["quant_us_min"], 1),

@@ -11,8 +11,8 @@
 extern "C" {
 #endif
 
-/* Runs `iters` rounds of 8 register-fed INT8 MFMAs (32x32x32) on each of
- * the 8 waves of `workgroups` workgroups, i.e. workgroups * 8 * iters * 8 * 65536 integer operations, with no
+/* Runs `iters` rounds of 16 register-fed INT8 MFMAs (16x16x64, the shape of the compute-bound GEMM tiles) on each of
+ * the 8 waves of `workgroups` workgroups, i.e. workgroups * 8 * iters * 16 * 32768 integer operations, with no
  * memory traffic inside the loop.  The operand registers are filled once from `data` (device int8, at least
  * workgroups * 49152 bytes: the bit patterns matter, the sustained clock depends on them); sink: device int32
  * [workgroups * 512], overwritten.  bench.py times it to report the GEMM against what the matrix pipes sustain. */

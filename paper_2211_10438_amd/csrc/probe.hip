@@ -7,37 +7,34 @@
 
 namespace {
 
-// 8 waves per workgroup (two per SIMD, like the prefill GEMM tiles), each with 8 independent 32x32 accumulator
-// blocks fed by 4 + 2 operand fragments taken once from `data` (so the operand bits are the caller's: random
-// int8 codes toggle far more wires than zeros do, and the sustained clock depends on it).
+// 8 waves per workgroup (two per SIMD, like the prefill GEMM tiles), each with 16 independent 16x16 accumulator
+// blocks (the MFMA shape of the compute-bound GEMM tiles) fed by six operand fragments taken once from `data` (so the
+// operand bits are the caller's: random int8 codes toggle far more wires than zeros do, and the sustained clock depends
+// on it): fragments 0..3 as one operand, 2..5 as the other.
 __global__ __launch_bounds__(512, 1) void mfma_probe_kernel(const v4i* __restrict__ data, int iters, int* __restrict__ sink)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    v4i fa[4], fb[2];
+    v4i f[6];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) fa[i] = data[((blockIdx.x * 8 + wave) * 6 + i) * 64 + lane];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) fb[j] = data[((blockIdx.x * 8 + wave) * 6 + 4 + j) * 64 + lane];
-    v16i acc[4][2];
+    for (int i = 0; i < 6; ++i) f[i] = data[((blockIdx.x * 8 + wave) * 6 + i) * 64 + lane];
+    v4i acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+        for (int j = 0; j < 4; ++j) acc[i][j] = v4i{0, 0, 0, 0};
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fb[j], fa[i], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(f[2 + j], f[i], acc[i][j], 0, 0, 0);
     }
     int s = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) s += acc[i][j][v];
+            for (int v = 0; v < 4; ++v) s += acc[i][j][v];
     sink[blockIdx.x * 512 + threadIdx.x] = s;
 }
 
