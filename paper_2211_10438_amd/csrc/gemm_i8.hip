@@ -364,10 +364,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
     // ---- 16x16x64 shape.  A wave owns 64 rows x WN columns.  Its four A fragments of a K step stay in registers for the
     // whole step (the next step's four are read meanwhile into a second set); the NI B fragments come in NP parts of
     // two, double buffered: while the 8 MFMAs of a part issue, the two fragments of the next part are read.
-    // Per step 4 + NI reads of 1 KB and 4 NI MFMAs.  The barrier that publishes stage it + 1 sits in front of part
-    // NP / 2; the reads that belong to the next step (its A fragments, its first part of B) come after it.
-    constexpr int NQ = 2, NP = NI / NQ, PB = NP / 2;
-    static_assert(NP % 2 == 0 && (NP - PB == 2 || NP - PB == 3), "parts of a K step");
+    // Per step 4 + NI reads of 1 KB and 4 NI MFMAs.  The barrier that publishes stage it + 1 sits in front of the third
+    // part from the end; the reads that belong to the next step (its A fragments, its first part of B) come after it.
+    constexpr int NQ = 2, NP = NI / NQ, PB = NP - 3;
+    static_assert(NP % 2 == 0 && PB >= 1, "parts of a K step");
     v4i fa[2][MI], fbq[2][NQ];
 #pragma unroll
     for (int s = 0; s < NSTAGE - 1; ++s) issue_stage(s < nk ? s : nk - 1, s);
@@ -397,10 +397,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
                 wait_vmcnt_imm<(NSTAGE - 3) * LPS>();
                 __builtin_amdgcn_s_barrier();
             }
-            // next step's A fragments: two in the first part behind the barrier, the rest over the parts that follow
+            // next step's A fragments: two each in the last two parts.  (None in the first part behind the barrier: there
+            // the eight waves run in step and their stage loads and reads meet in the LDS; with two of the four reads
+            // there the whole step took an eighth longer.)
             constexpr int pa = q - PB;  // parts behind the barrier so far
-            constexpr int an0 = pa <= 0 ? 0 : (NP - PB == 2 ? 2 * pa : pa + 1);
-            constexpr int an_cnt = pa < 0 ? 0 : (NP - PB == 2 ? 2 : (pa == 0 ? 2 : 1));
+            constexpr int an0 = pa <= 1 ? 0 : 2;
+            constexpr int an_cnt = pa <= 0 ? 0 : 2;
             // The part in the instruction stream, fixed by scheduling fences: its first MFMA (in front of it the wait
             // for this part's fragments, which is exact there: nothing younger is in flight), then the reads of the
             // next part and, behind the barrier, the stage's global->LDS loads, then the other seven MFMAs, which
