@@ -1,0 +1,51 @@
+"""The compute-bound GEMM tiles exist in two MFMA shapes: 16x16x64 (taken when the K range is an even number of whole
+64-byte steps and is not split) and 32x32x32 (everything else).  These shapes are chosen so that the planner's cost
+model picks the 256x256 and the 256x384 tile in each of the two forms (300 tokens = one full and one ragged row block;
+32760 / 49144 output channels = one round of 256 tiles with a ragged last column tile; 4096 resp. 4160 input
+channels = 64 resp. 65 K steps), in both operand layouts.  Sampled rows against the oracle: int32 accumulators exact,
+16-bit outputs with bias, ReLU and residual identical."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2211_10438_amd import binding as sq
+from paper_2211_10438_amd import synth
+from tests._util import assert_identical_16, BF16, F16, bits_from_dev, dev, random_bf16_bits, rows_to_tiled_dev, to_dev_16, torch_dtype, ulp_distance
+
+pytestmark = pytest.mark.gpu
+
+T = 300
+ROWS = np.array([0, 15, 16, 63, 64, 127, 128, 255, 256, 271, 299], dtype=np.int64)  # wave, block and tile borders
+
+
+@pytest.mark.parametrize("c_i,c_o,tiled,odt", [
+    (4096, 32760, False, F16),   # 256x256, 16x16x64
+    (4160, 32760, True, BF16),   # 256x256, 32x32x32 (65 K steps)
+    (4096, 49144, True, BF16),   # 256x384, 16x16x64
+    (4160, 49144, False, F16),   # 256x384, 32x32x32
+    (4112, 32760, False, BF16),  # 256x256, 32x32x32 with a K tail (row-major only)
+])
+def test_tile_forms_vs_oracle(c_i, c_o, tiled, odt):
+    print(f"[case] tile forms t={T} c_i={c_i} c_o={c_o} tiled={tiled} out={odt}", flush=True)
+    rng = np.random.default_rng(c_i + c_o)
+    xq = synth.int8_codes((T, c_i), 401)
+    wq = synth.int8_codes((c_o, c_i), 402)
+    xs = (rng.random(T, dtype=np.float32) + np.float32(0.5)) * np.float32(2e-3)
+    ws = np.array([3e-3], np.float32)
+    bias = synth.bias(c_o, 403)
+    res = random_bf16_bits((T, c_o), 404) if odt == BF16 else synth.normal_fp16((T, c_o), 404)
+    lay = sq.TILED if tiled else sq.ROW_MAJOR
+    xq_d, wq_d = (rows_to_tiled_dev(xq), rows_to_tiled_dev(wq)) if tiled else (dev(xq), dev(wq))
+    rows_d = torch.from_numpy(ROWS).cuda()
+
+    acc = sq.i8_gemm_i32(xq_d, wq_d, layout=lay)
+    assert np.array_equal(acc[rows_d].cpu().numpy(), oracle.i8_gemm_i32(np.ascontiguousarray(xq[ROWS]), wq))
+    del acc
+    for kw in (dict(), dict(bias=True, relu=True, residual=True)):
+        ref = oracle.w8a8_linear(xq, xs, wq, ws, odt, bias=bias if kw else None, residual_bits=res if kw else None,
+                                 relu=bool(kw), rows=ROWS)
+        y = sq.w8a8_linear(xq_d, dev(xs), wq_d, dev(ws), torch_dtype(odt), bias=dev(bias) if kw else None,
+                           residual=to_dev_16(res, odt) if kw else None, relu=bool(kw), layout=lay)
+        assert_identical_16(ulp_distance(bits_from_dev(y[rows_d]), ref[ROWS]))
+        del y
