@@ -49,3 +49,18 @@ def test_tile_forms_vs_oracle(c_i, c_o, tiled, odt):
                            residual=to_dev_16(res, odt) if kw else None, relu=bool(kw), layout=lay)
         assert_identical_16(ulp_distance(bits_from_dev(y[rows_d]), ref[ROWS]))
         del y
+
+
+def test_batched_product_on_the_16x16x64_tile():
+    """A batched Q K^T-shaped product with a long contraction (30 x [300, 2048] x [1024, 2048]^T): 240 tiles of 256x256
+    in one round against two rounds of 256x192, so the batched launch takes the 16x16x64 form; three batch entries
+    against the oracle, every element."""
+    b, m, n, k = 30, 300, 1024, 2048
+    print(f"[case] batched product b={b} m={m} n={n} k={k}", flush=True)
+    a = synth.int8_codes((b, m, k), 411)
+    kt = synth.int8_codes((b, n, k), 412)
+    alpha = float(np.float32(2e-4))
+    got = sq.w8a8_bmm(dev(a), dev(kt), True, alpha, torch.float16)
+    for i in (0, 13, 29):
+        ref = oracle.w8a8_bmm(a[i:i + 1], kt[i:i + 1], True, alpha, F16)
+        assert_identical_16(ulp_distance(bits_from_dev(got[i:i + 1]), ref), f"batch entry {i}")
