@@ -158,6 +158,28 @@ def other_configs(sq, torch):
     L2 = make_layer(sq, torch, "c2fc2", 512, 20480, 5120, 0.0, 1.0, 0.5, False, 9003, out_dtype=f16, nsets=3,
                     x=L1["sets"][0]["y"])
     out["config2_opt13b_fc2_512x20480x5120"] = linear_entry(L2)
+    # The same pair with FC2's input quantizer (static per-tensor step, Table 2's O3) fused into FC1's epilogue
+    # (sq_w8a8_linear_q8: the ReLU output leaves FC1 as int8 codes) against FC1 + a separate static quantize launch.
+    y_step = (L1["sets"][0]["y"].float().abs().max() / 127.0).reshape(1).contiguous()
+    S1, S2 = L1["sets"][0], L2["sets"][0]
+    run_quant(sq, L1, 0)
+
+    def fc1_fp16(i):
+        sq.w8a8_linear(S1["xq"], S1["x_scale"], L1["wq"], L1["w_scale"], f16, relu=True, out=S1["y"], workspace=L1["ws"], layout=sq.TILED)
+
+    def q_static(i):
+        sq.quantize_act(S1["y"], sq.PER_TENSOR_STATIC, static_scale=y_step, out=(S2["xq"], y_step), layout=sq.TILED)
+
+    def fc1_q8(i):
+        sq.w8a8_linear_q8(S1["xq"], S1["x_scale"], L1["wq"], L1["w_scale"], y_step, f16, relu=True, out=S2["xq"],
+                          workspace=L1["ws"], layout=sq.TILED, out_layout=sq.TILED)
+
+    a_us, _ = time_stats(torch, fc1_fp16)
+    b_us, _ = time_stats(torch, q_static)
+    c_us, _ = time_stats(torch, fc1_q8)
+    out["config2_fc1_with_fc2_quantizer_fused"] = {"fc1_fp16_out_us": round(a_us, 1), "static_quantize_us": round(b_us, 1),
+                                                   "fc1_int8_out_us": round(c_us, 1),
+                                                   "saved_us": round(a_us + b_us - c_us, 1)}
     del L, L1, L2
 
     def attention(bh, s_len, d, seed):

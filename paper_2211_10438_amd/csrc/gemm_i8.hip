@@ -598,17 +598,17 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
                 if (p.q8_step) {
                     // int8 output: quantize the eight 16-bit values of this chunk (they never straddle a
                     // 16-byte chunk of the tiled layout) and store 8 codes
-                    int cq[8];
+                    // (clamp + add of 1.5 * 2^23: the code in the low byte, the same integer as requant_code's rint + clamp)
+                    uint32_t cq[8];
 #pragma unroll
-                    for (int t = 0; t < 8; ++t) cq[t] = requant_code<BF16>(val[t >> 1] >> ((t & 1) * 16), rq);
+                    for (int t = 0; t < 8; ++t) cq[t] = code_bits(load16_bits<BF16>(val[t >> 1] >> ((t & 1) * 16)) * rq);
                     int8_t* dq = code_dst(p.q8_out, row, col, p.N, p.q8_tiled != 0);
                     if (vec_ok) {
-                        *(v2u*)dq = v2u{(uint32_t)(cq[0] & 0xff) | ((uint32_t)(cq[1] & 0xff) << 8) | ((uint32_t)(cq[2] & 0xff) << 16) | ((uint32_t)(cq[3] & 0xff) << 24),
-                                        (uint32_t)(cq[4] & 0xff) | ((uint32_t)(cq[5] & 0xff) << 8) | ((uint32_t)(cq[6] & 0xff) << 16) | ((uint32_t)(cq[7] & 0xff) << 24)};
+                        *(v2u*)dq = v2u{pack4_low_bytes(cq[0], cq[1], cq[2], cq[3]), pack4_low_bytes(cq[4], cq[5], cq[6], cq[7])};
                     } else {
 #pragma unroll
                         for (int t = 0; t < 8; ++t)
-                            if (col + t < p.N) dq[t] = (int8_t)cq[t];
+                            if (col + t < p.N) dq[t] = (int8_t)(cq[t] & 0xffu);
                     }
                     continue;
                 }
