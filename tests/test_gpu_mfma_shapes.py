@@ -25,6 +25,8 @@ ROWS = np.array([0, 15, 16, 63, 64, 127, 128, 255, 256, 271, 299], dtype=np.int6
     (4096, 49144, True, BF16),   # 256x384, 16x16x64
     (4160, 49144, False, F16),   # 256x384, 32x32x32
     (4112, 32760, False, BF16),  # 256x256, 32x32x32 with a K tail (row-major only)
+    (384, 49144, True, F16),     # 256x384, 16x16x64 on the shortest K range that form takes (6 steps: 3 in flight before the loop)
+    (640, 49144, False, BF16),   # 256x384, 16x16x64, 10 steps
 ])
 def test_tile_forms_vs_oracle(c_i, c_o, tiled, odt):
     print(f"[case] tile forms t={T} c_i={c_i} c_o={c_o} tiled={tiled} out={odt}", flush=True)
