@@ -66,3 +66,42 @@ def test_batched_product_on_the_16x16x64_tile():
     for i in (0, 13, 29):
         ref = oracle.w8a8_bmm(a[i:i + 1], kt[i:i + 1], True, alpha, F16)
         assert_identical_16(ulp_distance(bits_from_dev(got[i:i + 1]), ref), f"batch entry {i}")
+
+
+# Seeded shapes that the planner's cost model sends to the 256- and 384-wide tiles, about half of them in each MFMA form
+# (the general random sweep of test_gpu_random_shapes.py stays below one round of tiles and so on the 256x192 tile):
+# (t, c_i, c_o, tiled)
+WIDE_TILE_SHAPES = [
+    (768, 1904, 30064, False), (700, 2144, 24112, False), (255, 2416, 57112, False), (500, 1344, 41992, False),
+    (384, 384, 25456, True), (700, 576, 53440, True), (130, 2080, 62664, False), (129, 1600, 53552, False),
+    (513, 1408, 61968, True), (256, 2480, 53872, False), (512, 1664, 41280, True), (513, 1536, 60736, False),
+    (512, 2048, 25120, False), (255, 1664, 64000, True),
+]
+
+
+@pytest.mark.parametrize("t,c_i,c_o,tiled", WIDE_TILE_SHAPES)
+def test_random_shapes_on_the_wide_tiles(t, c_i, c_o, tiled):
+    print(f"[case] wide-tile sweep t={t} c_i={c_i} c_o={c_o} tiled={tiled}", flush=True)
+    seed = t * 131 + c_i * 7 + c_o
+    rng = np.random.default_rng(seed)
+    rows = np.unique(np.concatenate([rng.choice(t, size=6, replace=False), [0, min(t - 1, 127), min(t - 1, 128), t - 1]])).astype(np.int64)
+    odt = BF16 if rng.integers(0, 2) else F16
+    per_token, use_bias, relu, use_res = (bool(rng.integers(0, 2)) for _ in range(4))
+    xq = synth.int8_codes((t, c_i), seed + 1)
+    wq = synth.int8_codes((c_o, c_i), seed + 2)
+    xs = (rng.random(t if per_token else 1, dtype=np.float32) * np.float32(0.01) + np.float32(1e-3)).astype(np.float32)
+    ws = np.array([2e-3], np.float32)
+    bias = synth.bias(c_o, seed + 3) if use_bias else None
+    res = None
+    if use_res:
+        res = synth.normal_fp16((t, c_o), seed + 4) if odt == F16 else random_bf16_bits((t, c_o), seed + 4)
+    lay = sq.TILED if tiled else sq.ROW_MAJOR
+    xq_d, wq_d = (rows_to_tiled_dev(xq), rows_to_tiled_dev(wq)) if tiled else (dev(xq), dev(wq))
+    rows_d = torch.from_numpy(rows).cuda()
+    acc = sq.i8_gemm_i32(xq_d, wq_d, layout=lay)
+    assert np.array_equal(acc[rows_d].cpu().numpy(), oracle.i8_gemm_i32(np.ascontiguousarray(xq[rows]), wq))
+    del acc
+    ref = oracle.w8a8_linear(xq, xs, wq, ws, odt, bias=bias, residual_bits=res, relu=relu, rows=rows)
+    y = sq.w8a8_linear(xq_d, dev(xs), wq_d, dev(ws), torch_dtype(odt), bias=None if bias is None else dev(bias),
+                       residual=None if res is None else to_dev_16(res, odt), relu=relu, layout=lay)
+    assert_identical_16(ulp_distance(bits_from_dev(y[rows_d]), ref[rows]))
