@@ -62,7 +62,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
     constexpr int WM = BM / WGM, WN = BN / WGN, MI = WM / MF, NI = WN / MF;
     constexpr int AV = MF * MF / 64;  // accumulator registers per block
     constexpr int QG = AV / 4;        // runs of four neighbouring output columns a lane holds per block
-    static_assert(MF == 32 || (MF == 16 && !BT && !ONESHOT && MI == 4 && NI % 4 == 0), "MFMA shape");
+    static_assert(MF == 32 || (MF == 16 && !BT && !ONESHOT && MI == 4 && NI % 2 == 0 && NI >= 6), "MFMA shape");
     constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE = A_BYTES + B_BYTES;
     constexpr int RBA = BM / 16, RBB = BN / 16;  // 16-row blocks per operand tile
     constexpr int SA = (RBA + NW - 1) / NW, SB = (RBB + NW - 1) / NW;  // BT: SB raw 1 KB blocks of the [64, BN] B tile
@@ -367,7 +367,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
     // Per step 4 + NI reads of 1 KB and 4 NI MFMAs.  The barrier that publishes stage it + 1 sits in front of the third
     // part from the end; the reads that belong to the next step (its A fragments, its first part of B) come after it.
     constexpr int NQ = 2, NP = NI / NQ, PB = NP - 3;
-    static_assert(NP % 2 == 0 && PB >= 1, "parts of a K step");
+    static_assert(PB >= 0, "parts of a K step");
     v4i fa[2][MI], fbq[2][NQ];
 #pragma unroll
     for (int s = 0; s < NSTAGE - 1; ++s) issue_stage(s < nk ? s : nk - 1, s);
@@ -382,7 +382,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
     // valid LDS, values never used) and refills a buffer nobody reads.  The host sends only K ranges of an even number
     // of whole steps here (K % 128 == 0, no K split), so the loop runs in pairs and there is no second copy of the step
     // outside it (with one, the register allocation of the epilogue spilled hundreds of registers per lane).
-    auto step = [&](v4i(&cur)[MI], v4i(&nxt)[MI], int it, int buf) {
+    // P0: which of the two B fragment sets the step's first part finds filled (with an odd number of parts per step the
+    // two steps of the unrolled pair start on different sets).
+    auto step = [&](auto P0_, v4i(&cur)[MI], v4i(&nxt)[MI], int it, int buf) {
+        constexpr int P0 = decltype(P0_)::value;
         const int nbuf = buf + 1 == NSTAGE ? 0 : buf + 1;
         const char* sb = smem + buf * STAGE + fragB0;
         const char* sn = smem + nbuf * STAGE;
@@ -407,7 +410,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
             // for this part's fragments, which is exact there: nothing younger is in flight), then the reads of the
             // next part and, behind the barrier, the stage's global->LDS loads, then the other seven MFMAs, which
             // cover the latency of those reads.
-            acc[0][q * NQ] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fbq[q & 1][0], cur[0], acc[0][q * NQ], 0, 0, 0);
+            acc[0][q * NQ] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fbq[(q + P0) & 1][0], cur[0], acc[0][q * NQ], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
             if constexpr (q >= PB) {
                 // the stage's loads (the first SA are A blocks, the others B blocks), spread over the parts behind the
@@ -425,10 +428,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
             }
             if constexpr (q < NP - 1) {
 #pragma unroll
-                for (int k = 0; k < NQ; ++k) fbq[(q + 1) & 1][k] = *(const v4i*)(sb + ((q + 1) * NQ + k) * 1024);
+                for (int k = 0; k < NQ; ++k) fbq[(q + 1 + P0) & 1][k] = *(const v4i*)(sb + ((q + 1) * NQ + k) * 1024);
             } else {
 #pragma unroll
-                for (int k = 0; k < NQ; ++k) fbq[0][k] = *(const v4i*)(sn + fragB0 + k * 1024);
+                for (int k = 0; k < NQ; ++k) fbq[(q + 1 + P0) & 1][k] = *(const v4i*)(sn + fragB0 + k * 1024);
             }
 #pragma unroll
             for (int k = 0; k < an_cnt; ++k) nxt[an0 + k] = *(const v4i*)(sn + fragA0 + (an0 + k) * 1024);
@@ -438,15 +441,15 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
 #pragma unroll
                 for (int i = 0; i < MI; ++i)
                     if (k + i > 0)
-                        acc[i][q * NQ + k] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fbq[q & 1][k], cur[i], acc[i][q * NQ + k], 0, 0, 0);
+                        acc[i][q * NQ + k] = __builtin_amdgcn_mfma_i32_16x16x64_i8(fbq[(q + P0) & 1][k], cur[i], acc[i][q * NQ + k], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         });
     };
     int buf = 0;
     for (int it = 0; it < nk; it += 2) {
-        step(fa[0], fa[1], it, buf);
+        step(std::integral_constant<int, 0>{}, fa[0], fa[1], it, buf);
         buf = buf + 1 == NSTAGE ? 0 : buf + 1;
-        step(fa[1], fa[0], it + 1, buf);
+        step(std::integral_constant<int, NP & 1>{}, fa[1], fa[0], it + 1, buf);
         buf = buf + 1 == NSTAGE ? 0 : buf + 1;
     }
     }
@@ -664,7 +667,7 @@ struct Plan {
                  // 7: 128x128, three workgroups per CU (short K: the output stream dominates)
                  // 8: 128x128, K <= 128 fetched in one go, four workgroups per CU
                  // 9: 256x384 (a round of tiles saved on wide outputs)
-                 // 10, 11: 256x256 and 256x384 with the 16x16x64 MFMA
+                 // 10, 11, 12: 256x256, 256x384 and 256x192 with the 16x16x64 MFMA
     int bm, bn;
     int splits, iters_per_split;
     int tiles_m, tiles_n;
@@ -702,8 +705,9 @@ Plan make_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split,
         // is part of these figures): K steps x 0.59 + 6 (256x192: fewer MFMAs per operand fragment read), x 0.70 + 18
         // (256x256), x 1.12 + 8 (256x384: 192 accumulator registers per lane, the whole 160 KB of LDS, the epilogue in
         // two halves) with the 32x32x32 MFMA; the 256- and 384-wide tiles also exist with the 16x16x64 MFMA, which
-        // draws less power per multiply-accumulate: x 0.66 + 18 and x 1.03 + 8.  That form needs an even number of
-        // whole K steps and no K split (see the kernel); other shapes keep the 32x32x32 form.
+        // draws less power per multiply-accumulate: x 0.66 + 18 and x 1.03 + 8; the 192-wide one too, x 0.52 + 14 (a
+        // 5-stage ring: the barrier of a step sits at its start), taken from 192 K steps on.  That form needs an even
+        // number of whole K steps and no K split (see the kernel); other shapes keep the 32x32x32 form.
         pl.cfg = 0;
         pl.bm = 256;
         const bool mf16 = (K & 127) == 0;
@@ -712,7 +716,8 @@ Plan make_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split,
         const int64_t rounds192 = (tm * ((N + 191) / 192) * batch + kNumCU - 1) / kNumCU;
         const int64_t rounds384 = (tm * ((N + 383) / 384) * batch + kNumCU - 1) / kNumCU;
         const double nks = (double)((K + 63) / 64);
-        const double t192 = rounds192 * (nks * 0.588 + 6.0);
+        const bool mf16_192 = mf16 && nks >= 192.0;  // (its longer ring costs more per tile: it pays on long K ranges only)
+        const double t192 = rounds192 * (mf16_192 ? nks * 0.522 + 14.0 : nks * 0.588 + 6.0);
         const double t256 = rounds256 * (nks * (mf16 ? 0.66 : 0.70) + 18.0);
         const double t384 = rounds384 * (nks * (mf16 ? 1.03 : 1.12) + 8.0);
         double t_now = t256;
@@ -755,6 +760,7 @@ Plan make_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split,
     if ((K & 127) == 0 && splits == 1) {  // the 16x16x64 form of the tile
         if (pl.cfg == 0) pl.cfg = 10;
         if (pl.cfg == 9) pl.cfg = 11;
+        if (pl.cfg == 6 && K >= 192 * 64) pl.cfg = 12;
     }
     return pl;
 }
@@ -778,6 +784,7 @@ void launch_cfg(const Plan& pl, const GemmArgs& a, int batch, hipStream_t st, bo
         case 9: SQ_LAUNCH(256, 384, 2, 4, 4); break;
         case 10: SQ_LAUNCH_MF(256, 256, 4, 2, 4, 16); break;
         case 11: SQ_LAUNCH_MF(256, 384, 4, 2, 4, 16); break;
+        case 12: SQ_LAUNCH_MF(256, 192, 4, 2, 5, 16); break;
         case 8:
             if (tiled) sq_launch((gemm_i8_kernel<128, 128, 2, 2, 3, EPI, BF16, LAY_TILED, 4, true>), grid, dim3(256), 0, st, a);
             else sq_launch((gemm_i8_kernel<128, 128, 2, 2, 3, EPI, BF16, LAY_ROWS, 4, true>), grid, dim3(256), 0, st, a);

@@ -1,6 +1,6 @@
 """The compute-bound GEMM tiles exist in two MFMA shapes: 16x16x64 (taken when the K range is an even number of whole
 64-byte steps and is not split) and 32x32x32 (everything else).  These shapes are chosen so that the planner's cost
-model picks the 256x256 and the 256x384 tile in each of the two forms (300 tokens = one full and one ragged row block;
+model picks the 256x256, the 256x384 and the 256x192 tile in each of the two forms (300 tokens = one full and one ragged row block;
 32760 / 49144 output channels = one round of 256 tiles with a ragged last column tile; 4096 resp. 4160 input
 channels = 64 resp. 65 K steps), in both operand layouts.  Sampled rows against the oracle: int32 accumulators exact,
 16-bit outputs with bias, ReLU and residual identical."""
@@ -27,6 +27,8 @@ ROWS = np.array([0, 15, 16, 63, 64, 127, 128, 255, 256, 271, 299], dtype=np.int6
     (4112, 32760, False, BF16),  # 256x256, 32x32x32 with a K tail (row-major only)
     (384, 49144, True, F16),     # 256x384, 16x16x64 on the shortest K range that form takes (6 steps: 3 in flight before the loop)
     (640, 49144, False, BF16),   # 256x384, 16x16x64, 10 steps
+    (12288, 24568, True, BF16),  # 256x192, 16x16x64 (taken from 192 K steps on: an odd number of parts per step, 5-stage ring)
+    (12352, 24568, False, F16),  # 256x192, 32x32x32 (193 K steps)
 ])
 def test_tile_forms_vs_oracle(c_i, c_o, tiled, odt):
     print(f"[case] tile forms t={T} c_i={c_i} c_o={c_o} tiled={tiled} out={odt}", flush=True)
