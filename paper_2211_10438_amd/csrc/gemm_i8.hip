@@ -593,8 +593,16 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
             default: phase1(T_{}, T_{}, T_{}); break;
         }
         __syncthreads();
+        // int8 codes in the tiled layout leave in another order: a wave instruction covers 8 rows x 64 columns, which are
+        // 512 contiguous bytes of a 1 KB block (walking along a row it would write 64-byte pieces of eight blocks)
+        const bool q8_blocks = p.q8_step && p.q8_tiled && (BN % 64 == 0);
         for (int q = threadIdx.x; q < GR * CPR; q += NW * 64) {
-            const int r = q / CPR, c8 = (q - r * CPR) * 8;
+            int r = q / CPR, c8 = (q - r * CPR) * 8;
+            if (q8_blocks) {
+                const int blk = q >> 6, cb = blk % (BN / 64);
+                r = (blk / (BN / 64)) * 8 + ((q >> 3) & 7);
+                c8 = (cb * 8 + (q & 7)) * 8;
+            }
             const int row = m0 + g0 + r, col = n0 + c8;
             if (row < p.M && col < p.N) {
                 const v4u val = *(const v4u*)(smem + r * PITCH + c8 * 2);
