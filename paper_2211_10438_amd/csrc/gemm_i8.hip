@@ -710,7 +710,7 @@ Plan make_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split,
     else if (M > 128) {
         // Compute-bound shapes: time = rounds of tiles over the 256 CUs x cost of one tile; pick the cheapest width.
         // Cost of a tile in microseconds, measured on quantized Gaussian operands (the clock that the power cap allows
-        // is part of these figures): K steps x 0.59 + 6 (256x192: fewer MFMAs per operand fragment read), x 0.70 + 18
+        // is part of these figures): K steps x 0.59 + 10 (256x192: fewer MFMAs per operand fragment read), x 0.70 + 18
         // (256x256), x 1.12 + 8 (256x384: 192 accumulator registers per lane, the whole 160 KB of LDS, the epilogue in
         // two halves) with the 32x32x32 MFMA; the 256- and 384-wide tiles also exist with the 16x16x64 MFMA, which
         // draws less power per multiply-accumulate: x 0.66 + 18 and x 1.03 + 8; the 192-wide one too, x 0.52 + 14 (a
@@ -725,7 +725,7 @@ Plan make_plan(int64_t M, int64_t N, int64_t K, int64_t batch, bool allow_split,
         const int64_t rounds384 = (tm * ((N + 383) / 384) * batch + kNumCU - 1) / kNumCU;
         const double nks = (double)((K + 63) / 64);
         const bool mf16_192 = mf16 && nks >= 192.0;  // (its longer ring costs more per tile: it pays on long K ranges only)
-        const double t192 = rounds192 * (mf16_192 ? nks * 0.522 + 14.0 : nks * 0.588 + 6.0);
+        const double t192 = rounds192 * (mf16_192 ? nks * 0.522 + 14.0 : nks * 0.588 + 10.0);
         const double t256 = rounds256 * (nks * (mf16 ? 0.66 : 0.70) + 18.0);
         const double t384 = rounds384 * (nks * (mf16 ? 1.03 : 1.12) + 8.0);
         double t_now = t256;
