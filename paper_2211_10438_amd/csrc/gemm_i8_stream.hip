@@ -233,8 +233,9 @@ __global__ __launch_bounds__(NWAVE * 64, 1) void gemm_i8_stream_kernel(const Gem
 //    by two extra waves of each workgroup instead 75 us;
 //  * more requests in flight than the latency needs cost bandwidth: 9 interleaved 1 KB streams per wave deliver
 //    6.9 TB/s with 9 loads in flight per wave, 5.8 with 18, 5.3 with 27, 4.8 with 45.
-//  * v_mfma_i32_16x16x64_i8 issues every 48 cycles from one wave per SIMD and every 32 from two (the 32x32x32 shape
-//    does twice the work in 34-37): with 128 tokens a single compute wave per SIMD is bound by its MFMAs.
+//  * in a loop of this kind (fragment reads and MFMAs in one instruction stream) v_mfma_i32_16x16x64_i8 came out every 48
+//    cycles from one wave per SIMD and every 32 from two (from registers alone a wave issues one every 17): with 128
+//    tokens a single compute wave per SIMD is bound by its MFMAs.
 // In the tiled layout a 1 KB block is one MFMA operand as it lies in memory, so the compute waves fetch their weight
 // blocks with one 16-byte load per lane straight into registers (no LDS, no barrier, no other wave to wait for), D of
 // their K steps deep, about a dozen loads in flight.  Six compute waves = 3 unit groups x 2 K parities: wave (ug, kp)
