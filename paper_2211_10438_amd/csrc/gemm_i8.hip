@@ -433,8 +433,10 @@ __global__ __launch_bounds__(WGM* WGN * 64, OCC) void gemm_i8_kernel(const GemmA
 #pragma unroll
                 for (int k = 0; k < NQ; ++k) fbq[(q + 1 + P0) & 1][k] = *(const v4i*)(sn + fragB0 + k * 1024);
             }
-#pragma unroll
-            for (int k = 0; k < an_cnt; ++k) nxt[an0 + k] = *(const v4i*)(sn + fragA0 + (an0 + k) * 1024);
+            static_for<an_cnt>([&](auto K_) {
+                constexpr int k = an0 + decltype(K_)::value;
+                nxt[k] = *(const v4i*)(sn + fragA0 + k * 1024);
+            });
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int k = 0; k < NQ; ++k)
